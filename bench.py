@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the Lion Cub compressed-update hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic optimizer state that
+is already resident in HBM: every worker's local update + pack, the W-way aggregation,
+the apply (and, where the workload asks for it, momentum averaging) -- all through the C
+ABI of liblioncub.so.  Prints ONE JSON line: params/s for the step, the roofline of the
+dominant kernel (algorithmic bytes / its mean launch duration from HIP events on the
+launch stream) and the CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c0|c2|c3|c4]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c1")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 25, help="parameters in the oracle's sample (0: skip)")
+    ap.add_argument("--cpu-threads", type=int, default=0, help="0 = host cores available, capped at 16")
+    return ap.parse_args()
+
+
+class Kernel:
+    """One C-ABI call of the step with its algorithmic bytes and HIP-event timing."""
+
+    def __init__(self, name, fn, alg_bytes):
+        self.name, self.fn, self.alg_bytes = name, fn, alg_bytes
+        self.events = []
+
+    def launch(self, torch, timed):
+        if timed:
+            a = torch.cuda.Event(enable_timing=True)
+            b = torch.cuda.Event(enable_timing=True)
+            a.record()
+            self.fn()
+            b.record()
+            self.events.append((a, b))
+        else:
+            self.fn()
+
+    def mean_ms(self):
+        return sum(a.elapsed_time(b) for a, b in self.events) / max(1, len(self.events))
+
+
+def build_step(wl, torch, lc, synth):
+    """Allocate the workload on cuda:0 and return (kernels, state) for one step."""
+    dev = "cuda"
+    n, W = wl.n, wl.W
+    nw = (n + 63) // 64
+    hp = dict(beta1=wl.beta1, beta2=wl.beta2, lr=wl.lr, wd=wl.wd)
+    st = {}
+    step_no = [1]
+    kernels = []
+    if wl.mode == "prepacked":
+        q = synth.make_prepacked(n, W, seed=wl.seed, device=dev, agree=wl.agree)
+        s1 = synth.make_state(n, 1, seed=wl.seed + 1, device=dev, g_scale=1.4e-3, noise=0.0)
+        theta, m, g = s1["theta"], s1["m"], s1["g"]
+        st.update(q=q, theta=theta, m=m, g=g)
+        kernels.append(Kernel(
+            "vote_apply_1bit",
+            lambda: lc.lc_vote_apply_1bit(q, q.stride(0), W, n, step_no[0], lc.LC_TIE_ZERO, theta, hp["lr"], hp["wd"],
+                                          m, m.stride(0), g, g.stride(0), lc.LC_F32, 1, hp["beta2"]),
+            n * (W / 8 + 8 + 8 + 4)))
+        return kernels, st, step_no
+    s = synth.make_state(n, W, seed=wl.seed, device=dev, g_dtype=wl.g_dtype, noise=wl.noise, m_spread=wl.m_spread)
+    theta, m, g = s["theta"], s["m"], s["g"]
+    gd = lc.LC_BF16 if wl.g_dtype == "bf16" else lc.LC_F32
+    gb = 2 if wl.g_dtype == "bf16" else 4
+    st.update(theta=theta, m=m, g=g)
+    if wl.mode == "1bit":
+        q = torch.zeros((W, synth.round_up(nw, 8)), dtype=torch.int64, device=dev)
+        st["q"] = q
+        kernels.append(Kernel(
+            "local_update_pack",
+            lambda: lc.lc_local_update_pack(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], 1, hp["beta2"], 1, q,
+                                            q.stride(0) * 8, step_no[0], lc.LC_ZERO_ALT),
+            W * n * (4 + gb + 4 + 1 / 8)))
+        kernels.append(Kernel(
+            "vote_apply_1bit",
+            lambda: lc.lc_vote_apply_1bit(q, q.stride(0), W, n, step_no[0], lc.LC_TIE_ZERO, theta, hp["lr"], hp["wd"],
+                                          None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
+            n * (W / 8 + 8)))
+    else:
+        C = lc.lc_container_bits(wl.p)
+        fb = (n * C + 7) // 8
+        q = torch.zeros((W, synth.round_up(fb, 64)), dtype=torch.uint8, device=dev)
+        sum_out = torch.zeros(synth.round_up(fb, 64), dtype=torch.uint8, device=dev)
+        st.update(q=q, sum_out=sum_out)
+        kernels.append(Kernel(
+            "local_update_pack",
+            lambda: lc.lc_local_update_pack(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], 1, hp["beta2"], C, q,
+                                            q.stride(0), step_no[0], lc.LC_ZERO_ALT),
+            W * n * (4 + gb + 4 + C / 8)))
+        kernels.append(Kernel(
+            "pbit_sum_apply",
+            lambda: lc.lc_pbit_sum_apply(q, q.stride(0), C, W, n, wl.p, sum_out, step_no[0], lc.LC_TIE_ZERO, theta,
+                                         hp["lr"], hp["wd"], None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
+            n * (W * C / 8 + C / 8 + 8)))
+    if wl.momentum_avg:
+        kernels.append(Kernel("momentum_avg", lambda: lc.lc_momentum_avg(m, m.stride(0), W, n), n * W * 8))
+    return kernels, st, step_no
+
+
+def cpu_baseline(wl, st, torch, sample, threads):
+    """The oracle, as it stands, on the first `sample` parameters of the same buffers,
+    split into contiguous chunks over host threads (the C loops release the GIL)."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    import numpy as np
+
+    import oracle as orc
+    n = min(wl.n, sample)
+    n -= n % 64
+    cores = threads or min(16, len(os.sched_getaffinity(0)))
+    kw = dict(beta1=wl.beta1, beta2=wl.beta2, lr=wl.lr, wd=wl.wd, step=1)
+    theta = st["theta"][:n].cpu().numpy()
+    if wl.mode == "prepacked":
+        words = st["q"][:, : n // 64].cpu().numpy().view(np.uint64)
+        m = st["m"][:, :n].cpu().numpy()
+        g = st["g"][:, :n].cpu().numpy()
+
+        def work(lo, hi):
+            b = np.stack([orc.unpack_1bit(words[w, lo // 64: hi // 64], hi - lo) for w in range(wl.W)])
+            K, S, u = orc.count_sign(b, 1, orc.TIE_ZERO)
+            orc.apply(theta[lo:hi], u, wl.lr, wl.wd)
+            orc.momentum(m[0, lo:hi], g[0, lo:hi], wl.beta2)
+    else:
+        m = st["m"][:, :n].cpu().numpy()
+        if wl.g_dtype == "bf16":
+            g = st["g"][:, :n].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+            gd = orc.BF16
+        else:
+            g = st["g"][:, :n].cpu().numpy()
+            gd = orc.F32
+
+        def work(lo, hi):
+            if wl.mode == "1bit":
+                r = orc.step_1bit(theta[lo:hi], m[:, lo:hi], g[:, lo:hi], g_dtype=gd, **kw)
+            else:
+                r = orc.step_pbit(theta[lo:hi], m[:, lo:hi], g[:, lo:hi], p=wl.p, g_dtype=gd, **kw)
+            if wl.momentum_avg:
+                orc.momentum_avg(r["m"].astype(np.float32))
+    chunk = max(64, (n // (cores * 4)) // 64 * 64)
+    spans = [(lo, min(n, lo + chunk)) for lo in range(0, n, chunk)]
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=cores) as ex:
+        list(ex.map(lambda s: work(*s), spans))
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "params/s", "cores": cores, "kind": "oracle",
+            "sample": "first %d params of %s, all %d workers, %d chunks over %d threads, %.2f s"
+                      % (n, wl.name, wl.W, len(spans), cores, dt)}
+
+
+def read_traffic(workload, kernel):
+    """HBM bytes per launch measured offline with rocprofv3 counters, if a summary for
+    this workload and kernel has been committed under profiles/."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split("=")
+        if len(parts) == 2 and parts[0].strip() == "traffic_bytes_per_launch." + kernel:
+            return float(parts[1])
+    return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the W workers are simulated as W buffers in one GPU's HBM); "
+                 "--gpus %d is not supported" % args.gpus)
+    import torch
+
+    import paper_2411_16462_amd as lc
+    from paper_2411_16462_amd import synth
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    lc.load()
+    torch.cuda.set_device(0)
+    wl = synth.workload(args.workload)
+    kernels, st, step_no = build_step(wl, torch, lc, synth)
+    torch.cuda.synchronize()
+
+    def one_step(timed):
+        for k in kernels:
+            k.launch(torch, timed)
+        step_no[0] += 1
+
+    for _ in range(args.warmup):
+        one_step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    per_kernel = []
+    for k in kernels:
+        ms = k.mean_ms()
+        per_kernel.append({"kernel": k.name, "ms": ms, "alg_bytes": k.alg_bytes,
+                           "achieved_GBps": k.alg_bytes / (ms * 1e-3) / 1e9})
+    dom = max(per_kernel, key=lambda r: r["ms"])
+    roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["achieved_GBps"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": dom["achieved_GBps"] / HBM_PEAK_GBS,
+                "traffic": read_traffic(wl.name, dom["kernel"])}
+    step_bytes = sum(k.alg_bytes for k in kernels)
+    out = {
+        "metric": "params/sec for Lion Cub step (pack+W-way vote+apply); % of HBM peak GB/s",
+        "value": wl.n / (ms_per_step * 1e-3), "unit": "params/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "n_params": wl.n, "workers": wl.W, "mode": wl.mode, "p": wl.p,
+                   "g_dtype": wl.g_dtype, "momentum_avg": wl.momentum_avg},
+        "step_alg_bytes": step_bytes, "step_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "roofline": roofline, "kernels": per_kernel,
+    }
+    if args.cpu_sample > 0:
+        out["cpu_baseline"] = cpu_baseline(wl, st, torch, args.cpu_sample, args.cpu_threads)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,143 @@
+/*
+ * lioncub.h -- C ABI of the MI355X (gfx950) library for the data-parallel hot path of
+ * Lion Cub's compressed update step ("Lion Cub: Minimizing Communication Overhead for
+ * Distributed Lion", arXiv 2411.16462; Algorithm 1 and Section 3).
+ *
+ * W simulated workers live on one GPU as W rows of gradient / momentum / packed-sign
+ * buffers in device memory; the W-way aggregation is the local reduction that one
+ * GPU performs on its share after the exchange of Section 3.
+ *
+ * Conventions that hold for every entry point
+ *  - All data pointers are DEVICE pointers owned by the caller.  The library allocates
+ *    nothing, keeps no state between calls, never frees or retains caller memory and
+ *    never synchronises.  `stream` is a hipStream_t passed as void* (NULL = the null
+ *    stream); every call only enqueues kernels on it and returns.
+ *  - Row w of a per-worker buffer starts at base + w * stride.
+ *  - theta and m are fp32.  g is fp32 (LC_F32) or bfloat16 (LC_BF16, widened exactly).
+ *  - n counts the elements of one contiguous range (a flat arena, as the paper
+ *    consolidates all gradients into one tensor, or one tensor of it).  n = 0 is a
+ *    successful no-op.  A range handed to separate calls must start at an element
+ *    offset that is a multiple of 64 so that packed words do not straddle calls.
+ *  - 1-bit layout: element i is bit (i mod 64) of 64-bit word floor(i/64), least
+ *    significant bit first -- the order of a wave64 lane mask.  ceil(n/64) words per
+ *    row; bits past n in the last word are written as 0 and ignored on input.
+ *  - p-bit layout (Appendix F.1: sub-byte entries are packed into a uint8 and the width
+ *    must divide the container): a value of p bits sits in a field of C = 1, 2, 4 or 8
+ *    bits, the smallest that holds p (p = 7 -> one byte).  Element i is field
+ *    (i mod 8/C) of byte floor(i*C/8), low bits first; ceil(n*C/8) bytes per row; pad
+ *    fields are written as 0.  Bytes past that count are neither read nor written.
+ *  - Alignment: theta, m, g, field buffers and sum_out: base and every row 16-byte
+ *    aligned.  1-bit buffers and vote planes: 8-byte aligned.
+ *  - `step` is the caller's 1-based iteration counter; only its parity is used, by the
+ *    alternating rule of Appendix B.1 (zero -> +1 on odd iterations, -1 on even ones).
+ *  - Buffers named in one call must not overlap each other.
+ *  - Return value: LC_OK, or a positive LC_ERR_* found on the host before anything was
+ *    launched (nothing was written), or -(hipError_t) if a launch failed.
+ *  - Thread safety: re-entrant; calls on different streams may run concurrently as
+ *    long as their buffers are disjoint.
+ */
+#ifndef LIONCUB_H
+#define LIONCUB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LC_MAX_W 255 /* most workers one aggregation call accepts (counts fit 8 bits) */
+
+enum {
+    LC_OK = 0,
+    LC_ERR_NULL = 1,  /* a required pointer is NULL                                      */
+    LC_ERR_SIZE = 2,  /* W < 1, W > LC_MAX_W, n_m out of range                           */
+    LC_ERR_ALIGN = 3, /* a base pointer or a row stride breaks the alignment rules       */
+    LC_ERR_RANGE = 4, /* p outside 1..8, or W > 2^p - 1 (the p-bit sum could overflow)   */
+    LC_ERR_DTYPE = 5, /* unknown gradient dtype                                          */
+    LC_ERR_MODE = 6   /* unknown rule, out_bits / in_bits not one of the allowed widths  */
+};
+enum { LC_F32 = 0, LC_BF16 = 1 };
+/* What an exact zero of sign(c) becomes when it has to fit one bit (Section 3 "forcing
+ * 0 to be one or the other"; Appendix B.1 alternates by iteration parity). */
+enum { LC_ZERO_ALT = 0, LC_ZERO_POS = 1, LC_ZERO_NEG = 2 };
+/* What a tied vote becomes: 0 (the sign of a zero sum, Algorithm 1 line 5; needs the
+ * nz plane), or the alternating sign of Appendix B.1 (fits one bit again). */
+enum { LC_TIE_ZERO = 0, LC_TIE_ALT = 1 };
+
+/* Algorithm 1 lines 3 and 6 plus the quantiser Q = sign, for all W workers in one
+ * launch: c = beta1 * m_w + (1 - beta1) * g_w in fp32 as fma(beta1, m, fl((1-beta1)*g));
+ * bit = 1 if c > 0, 0 if c < 0, the zero rule's bit if c == 0 (or NaN).
+ *   out_bits = 1: q row w receives the 1-bit words.  out_bits = 2, 4, 8: the bit is
+ *   stored as a 0/1 value in fields of that many bits ({-1,+1} -> {0,1}, Appendix F.1).
+ *   q = NULL skips the packed output (then update_m must be set).
+ *   update_m != 0: m_w <- beta2 * m_w + (1 - beta2) * g_w in place, from the same loads
+ *   (line 6 reads the momentum line 3 read, so fusing changes no result).
+ * g: rows of g_dtype, read only.  m: rows of fp32, read (and written if update_m). */
+int lc_local_update_pack(const void *g, size_t g_stride_elems, int g_dtype,
+                         float *m, size_t m_stride_elems, int W, size_t n, float beta1,
+                         int update_m, float beta2, int out_bits, void *q,
+                         size_t q_stride_bytes, uint64_t step, int zero_rule, void *stream);
+
+/* Section 3, local part of the 1-bit compressed allreduce, and Appendix A.1: majority
+ * vote over W 1-bit rows.  K_i = number of rows with bit i set, S_i = 2 K_i - W,
+ * u_i = sign(S_i), a tie following tie_rule.  Output: two planes in the 1-bit layout,
+ * vote_pos bit = (u > 0), vote_nz bit = (u != 0); either may be NULL. */
+int lc_vote_1bit(const uint64_t *q, size_t q_stride_words, int W, size_t n,
+                 uint64_t *vote_pos, uint64_t *vote_nz, uint64_t step, int tie_rule,
+                 void *stream);
+
+/* Section 3 "direct allreduce" / Appendix F.1: the p-bit sum of the workers' 0/1 signs,
+ * then the sign of the sum of signs.  Requires 1 <= p <= 8 and W <= 2^p - 1.
+ *   in_bits = container(p): q rows are p-bit field buffers; they are added field-wise.
+ *   in_bits = 1:            q rows are 1-bit buffers (q_stride_bytes a multiple of 8).
+ *   sum_out (may be NULL): K as container(p)-bit fields, ceil(n*C/8) bytes.
+ *   vote_pos / vote_nz (may be NULL): as in lc_vote_1bit. */
+int lc_pbit_sum_sign(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n,
+                     int p, void *sum_out, uint64_t *vote_pos, uint64_t *vote_nz,
+                     uint64_t step, int tie_rule, void *stream);
+
+/* Algorithm 1 line 5 (read as Lion's decoupled weight decay) and line 6:
+ *   theta <- theta - lr * (u + wd * theta), u from the planes (vote_nz = NULL: every
+ *   element is non-zero, u = +1 where the pos bit is set and -1 elsewhere);
+ *   for w < n_m: m_w <- beta2 * m_w + (1 - beta2) * g_w.  n_m = 0 leaves m and g unused
+ *   (they may be NULL). */
+int lc_apply_update(float *theta, const uint64_t *vote_pos, const uint64_t *vote_nz,
+                    size_t n, float lr, float wd, float *m, size_t m_stride_elems,
+                    const void *g, size_t g_stride_elems, int g_dtype, int n_m,
+                    float beta2, void *stream);
+
+/* Section 5, momentum synchronisation: every row becomes the mean of the W rows (what
+ * an averaging allreduce leaves on every worker).  fp32 sum in row order, then one
+ * multiplication by 1/W. */
+int lc_momentum_avg(float *m, size_t m_stride_elems, int W, size_t n, void *stream);
+
+/* Fused forms: lc_vote_1bit followed by lc_apply_update without writing the planes. */
+int lc_vote_apply_1bit(const uint64_t *q, size_t q_stride_words, int W, size_t n,
+                       uint64_t step, int tie_rule, float *theta, float lr, float wd,
+                       float *m, size_t m_stride_elems, const void *g,
+                       size_t g_stride_elems, int g_dtype, int n_m, float beta2,
+                       void *stream);
+
+/* lc_pbit_sum_sign followed by lc_apply_update without writing the planes; sum_out as
+ * in lc_pbit_sum_sign (may be NULL). */
+int lc_pbit_sum_apply(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n,
+                      int p, void *sum_out, uint64_t step, int tie_rule, float *theta,
+                      float lr, float wd, float *m, size_t m_stride_elems, const void *g,
+                      size_t g_stride_elems, int g_dtype, int n_m, float beta2,
+                      void *stream);
+
+/* Smallest field width of 1, 2, 4, 8 bits that holds a p-bit value; -1 if p is not in
+ * 1..8.  Host only. */
+int lc_container_bits(int p);
+
+/* Static, human-readable name of a status code returned by the calls above. */
+const char *lc_status_string(int status);
+
+/* Library version as major * 10000 + minor * 100 + patch. */
+int lc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIONCUB_H */

@@ -1,0 +1,141 @@
+"""Python binding of liblioncub.so (include/lioncub.h): argument marshalling only.
+
+Every function has the name and the argument order of its C entry point.  Pointer
+arguments take a torch tensor on the GPU (its ``data_ptr()`` is passed), ``None`` (NULL)
+or an integer device address.  ``stream=None`` means torch's current stream.  A non-zero
+status raises ``LionCubError`` unless ``check=False`` is given, in which case the status
+is returned.
+
+PyTorch is used for device memory and streams only; every step of the path runs in the
+library's kernels.  There is no fallback: if the library has not been built
+(``python paper_2411_16462_amd/build.py``) the first call raises.
+"""
+import ctypes as C
+import os
+
+LC_OK, LC_ERR_NULL, LC_ERR_SIZE, LC_ERR_ALIGN, LC_ERR_RANGE, LC_ERR_DTYPE, LC_ERR_MODE = range(7)
+LC_F32, LC_BF16 = 0, 1
+LC_ZERO_ALT, LC_ZERO_POS, LC_ZERO_NEG = 0, 1, 2
+LC_TIE_ZERO, LC_TIE_ALT = 0, 1
+LC_MAX_W = 255
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblioncub.so")
+
+_vp, _sz, _i, _u64, _f = C.c_void_p, C.c_size_t, C.c_int, C.c_uint64, C.c_float
+
+# name -> (restype, argtypes); mirrors include/lioncub.h
+SIGNATURES = {
+    "lc_local_update_pack": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _i, _f, _i, _vp, _sz, _u64, _i, _vp]),
+    "lc_vote_1bit": (_i, [_vp, _sz, _i, _sz, _vp, _vp, _u64, _i, _vp]),
+    "lc_pbit_sum_sign": (_i, [_vp, _sz, _i, _i, _sz, _i, _vp, _vp, _vp, _u64, _i, _vp]),
+    "lc_apply_update": (_i, [_vp, _vp, _vp, _sz, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
+    "lc_momentum_avg": (_i, [_vp, _sz, _i, _sz, _vp]),
+    "lc_vote_apply_1bit": (_i, [_vp, _sz, _i, _sz, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
+    "lc_pbit_sum_apply": (_i, [_vp, _sz, _i, _i, _sz, _i, _vp, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i,
+                               _f, _vp]),
+    "lc_container_bits": (_i, [_i]),
+    "lc_status_string": (C.c_char_p, [_i]),
+    "lc_version": (_i, []),
+}
+
+_lib = None
+
+
+class LionCubError(RuntimeError):
+    def __init__(self, name, status, text):
+        super().__init__("%s failed with status %d (%s)" % (name, status, text))
+        self.status = status
+
+
+def load():
+    """Load the HIP library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        import torch  # noqa: F401  -- first, so that the process uses torch's HIP runtime
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s is missing: build it with `python paper_2411_16462_amd/build.py`; "
+                              "there is no fallback path" % LIB_PATH)
+        lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if not x.is_cuda:
+        raise ValueError("pointer arguments must be GPU tensors")
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _call(name, check, *args):
+    lib = load()
+    rc = getattr(lib, name)(*args)
+    if rc != LC_OK and check:
+        raise LionCubError(name, rc, lib.lc_status_string(rc).decode())
+    return rc
+
+
+def lc_local_update_pack(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, update_m, beta2,
+                         out_bits, q, q_stride_bytes, step, zero_rule, stream=None, check=True):
+    return _call("lc_local_update_pack", check, _ptr(g), g_stride_elems, g_dtype, _ptr(m), m_stride_elems, W, n,
+                 beta1, int(update_m), beta2, out_bits, _ptr(q), q_stride_bytes, step, zero_rule, _stream(stream))
+
+
+def lc_vote_1bit(q, q_stride_words, W, n, vote_pos, vote_nz, step, tie_rule, stream=None, check=True):
+    return _call("lc_vote_1bit", check, _ptr(q), q_stride_words, W, n, _ptr(vote_pos), _ptr(vote_nz), step,
+                 tie_rule, _stream(stream))
+
+
+def lc_pbit_sum_sign(q, q_stride_bytes, in_bits, W, n, p, sum_out, vote_pos, vote_nz, step, tie_rule,
+                     stream=None, check=True):
+    return _call("lc_pbit_sum_sign", check, _ptr(q), q_stride_bytes, in_bits, W, n, p, _ptr(sum_out),
+                 _ptr(vote_pos), _ptr(vote_nz), step, tie_rule, _stream(stream))
+
+
+def lc_apply_update(theta, vote_pos, vote_nz, n, lr, wd, m, m_stride_elems, g, g_stride_elems, g_dtype, n_m,
+                    beta2, stream=None, check=True):
+    return _call("lc_apply_update", check, _ptr(theta), _ptr(vote_pos), _ptr(vote_nz), n, lr, wd, _ptr(m),
+                 m_stride_elems, _ptr(g), g_stride_elems, g_dtype, n_m, beta2, _stream(stream))
+
+
+def lc_momentum_avg(m, m_stride_elems, W, n, stream=None, check=True):
+    return _call("lc_momentum_avg", check, _ptr(m), m_stride_elems, W, n, _stream(stream))
+
+
+def lc_vote_apply_1bit(q, q_stride_words, W, n, step, tie_rule, theta, lr, wd, m, m_stride_elems, g,
+                       g_stride_elems, g_dtype, n_m, beta2, stream=None, check=True):
+    return _call("lc_vote_apply_1bit", check, _ptr(q), q_stride_words, W, n, step, tie_rule, _ptr(theta), lr, wd,
+                 _ptr(m), m_stride_elems, _ptr(g), g_stride_elems, g_dtype, n_m, beta2, _stream(stream))
+
+
+def lc_pbit_sum_apply(q, q_stride_bytes, in_bits, W, n, p, sum_out, step, tie_rule, theta, lr, wd, m,
+                      m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream=None, check=True):
+    return _call("lc_pbit_sum_apply", check, _ptr(q), q_stride_bytes, in_bits, W, n, p, _ptr(sum_out), step,
+                 tie_rule, _ptr(theta), lr, wd, _ptr(m), m_stride_elems, _ptr(g), g_stride_elems, g_dtype, n_m,
+                 beta2, _stream(stream))
+
+
+def lc_container_bits(p):
+    return load().lc_container_bits(p)
+
+
+def lc_status_string(status):
+    return load().lc_status_string(status).decode()
+
+
+def lc_version():
+    return load().lc_version()

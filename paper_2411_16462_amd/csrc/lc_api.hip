@@ -1,0 +1,212 @@
+// C ABI of the library: argument validation on the host, then one kernel launch per
+// call.  Nothing here allocates, synchronises or keeps state.
+#include "lc_launch.hpp"
+
+namespace lc {
+
+
+namespace {
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline int from_hip(hipError_t e) { return e == hipSuccess ? LC_OK : -static_cast<int>(e); }
+inline size_t gbytes(int g_dtype) { return g_dtype == LC_BF16 ? 2 : 4; }
+
+int container(int p)
+{
+    if (p < 1 || p > 8) return -1;
+    return p == 1 ? 1 : p == 2 ? 2 : p <= 4 ? 4 : 8;
+}
+
+// rows of fp32 momentum and of gradients, `rows` of them
+int check_mg(const float *m, size_t m_stride, const void *g, size_t g_stride, int g_dtype, int rows)
+{
+    if (g_dtype != LC_F32 && g_dtype != LC_BF16) return LC_ERR_DTYPE;
+    if (!m || !g) return LC_ERR_NULL;
+    if (!aligned(m, 16) || !aligned(g, 16)) return LC_ERR_ALIGN;
+    if (rows > 1 && ((m_stride * 4) % 16 != 0 || (g_stride * gbytes(g_dtype)) % 16 != 0)) return LC_ERR_ALIGN;
+    return LC_OK;
+}
+
+int tie_code(int tie_rule, uint64_t step)
+{
+    if (tie_rule == LC_TIE_ZERO) return -1;
+    return (step & 1u) ? 1 : 0;
+}
+
+// shared by the four aggregation entry points
+int aggregate(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n, int p, void *sum_out, uint64_t *vote_pos,
+              uint64_t *vote_nz, uint64_t step, int tie_rule, bool apply, float *theta, float lr, float wd, float *m,
+              size_t m_stride, const void *g, size_t g_stride, int g_dtype, int n_m, float beta2, void *stream)
+{
+    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    if (tie_rule != LC_TIE_ZERO && tie_rule != LC_TIE_ALT) return LC_ERR_MODE;
+    int sum_bits = 0;
+    if (p != 0) {  // p-bit sum: range rule of the direct allreduce
+        sum_bits = container(p);
+        if (sum_bits < 0) return LC_ERR_RANGE;
+        if (W > (1 << p) - 1) return LC_ERR_RANGE;
+        if (in_bits != 1 && in_bits != sum_bits) return LC_ERR_MODE;
+    } else if (in_bits != 1) {
+        return LC_ERR_MODE;
+    }
+    if (!q) return LC_ERR_NULL;
+    if (in_bits == 1) {
+        if (!aligned(q, 8) || (W > 1 && q_stride_bytes % 8 != 0)) return LC_ERR_ALIGN;
+    } else {
+        if (!aligned(q, 16) || (W > 1 && q_stride_bytes % 16 != 0)) return LC_ERR_ALIGN;
+    }
+    if (sum_out && !aligned(sum_out, 16)) return LC_ERR_ALIGN;
+    if (!aligned(vote_pos, 8) || !aligned(vote_nz, 8)) return LC_ERR_ALIGN;
+    if (apply) {
+        if (!theta) return LC_ERR_NULL;
+        if (!aligned(theta, 16)) return LC_ERR_ALIGN;
+        if (n_m < 0 || n_m > LC_MAX_W) return LC_ERR_SIZE;
+        if (n_m > 0) {
+            const int rc = check_mg(m, m_stride, g, g_stride, g_dtype, n_m);
+            if (rc) return rc;
+        }
+    }
+    if (n == 0) return LC_OK;
+    AggParams P{};
+    P.q = q;
+    P.q_stride_bytes = q_stride_bytes;
+    P.W = W;
+    P.n = n;
+    P.sum_bits = sum_bits;
+    P.sum_out = sum_out;
+    P.vote_pos = vote_pos;
+    P.vote_nz = vote_nz;
+    P.tie = tie_code(tie_rule, step);
+    P.theta = theta;
+    P.lr = lr;
+    P.wd = wd;
+    P.m = m;
+    P.m_stride = m_stride;
+    P.g = g;
+    P.g_stride = g_stride;
+    P.n_m = apply ? n_m : 0;
+    P.beta2 = beta2;
+    P.omb2 = 1.0f - beta2;
+    const bool kout = in_bits == 1 && sum_out != nullptr;
+    return from_hip(launch_aggregate(P, in_bits, apply, kout, (apply && n_m > 0) ? g_dtype : LC_F32,
+                                     static_cast<hipStream_t>(stream)));
+}
+
+}  // namespace
+}  // namespace lc
+
+using namespace lc;
+
+extern "C" {
+
+int lc_local_update_pack(const void *g, size_t g_stride_elems, int g_dtype, float *m, size_t m_stride_elems, int W,
+                         size_t n, float beta1, int update_m, float beta2, int out_bits, void *q, size_t q_stride_bytes,
+                         uint64_t step, int zero_rule, void *stream)
+{
+    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    if (out_bits != 1 && out_bits != 2 && out_bits != 4 && out_bits != 8) return LC_ERR_MODE;
+    if (zero_rule != LC_ZERO_ALT && zero_rule != LC_ZERO_POS && zero_rule != LC_ZERO_NEG) return LC_ERR_MODE;
+    if (!q && !update_m) return LC_ERR_NULL;
+    const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
+    if (rc) return rc;
+    if (q) {
+        const size_t a = out_bits == 1 ? 8 : 16;
+        if (!aligned(q, a) || (W > 1 && q_stride_bytes % a != 0)) return LC_ERR_ALIGN;
+    }
+    if (n == 0) return LC_OK;
+    const int zero_bit = zero_rule == LC_ZERO_POS ? 1 : zero_rule == LC_ZERO_NEG ? 0 : static_cast<int>(step & 1u);
+    return from_hip(launch_local_update_pack(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, update_m != 0, beta2,
+                                             out_bits, q, q_stride_bytes, zero_bit, static_cast<hipStream_t>(stream)));
+}
+
+int lc_vote_1bit(const uint64_t *q, size_t q_stride_words, int W, size_t n, uint64_t *vote_pos, uint64_t *vote_nz,
+                 uint64_t step, int tie_rule, void *stream)
+{
+    return aggregate(q, q_stride_words * 8, 1, W, n, 0, nullptr, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f, 0.0f,
+                     nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream);
+}
+
+int lc_pbit_sum_sign(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n, int p, void *sum_out,
+                     uint64_t *vote_pos, uint64_t *vote_nz, uint64_t step, int tie_rule, void *stream)
+{
+    if (p == 0) return LC_ERR_RANGE;
+    return aggregate(q, q_stride_bytes, in_bits, W, n, p, sum_out, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f,
+                     0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream);
+}
+
+int lc_vote_apply_1bit(const uint64_t *q, size_t q_stride_words, int W, size_t n, uint64_t step, int tie_rule, float *theta,
+                       float lr, float wd, float *m, size_t m_stride_elems, const void *g, size_t g_stride_elems, int g_dtype,
+                       int n_m, float beta2, void *stream)
+{
+    return aggregate(q, q_stride_words * 8, 1, W, n, 0, nullptr, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
+                     m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
+}
+
+int lc_pbit_sum_apply(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n, int p, void *sum_out, uint64_t step,
+                      int tie_rule, float *theta, float lr, float wd, float *m, size_t m_stride_elems, const void *g,
+                      size_t g_stride_elems, int g_dtype, int n_m, float beta2, void *stream)
+{
+    if (p == 0) return LC_ERR_RANGE;
+    return aggregate(q, q_stride_bytes, in_bits, W, n, p, sum_out, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
+                     m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
+}
+
+int lc_apply_update(float *theta, const uint64_t *vote_pos, const uint64_t *vote_nz, size_t n, float lr, float wd, float *m,
+                    size_t m_stride_elems, const void *g, size_t g_stride_elems, int g_dtype, int n_m, float beta2,
+                    void *stream)
+{
+    if (!theta || !vote_pos) return LC_ERR_NULL;
+    if (!aligned(theta, 16) || !aligned(vote_pos, 8) || !aligned(vote_nz, 8)) return LC_ERR_ALIGN;
+    if (n_m < 0 || n_m > LC_MAX_W) return LC_ERR_SIZE;
+    if (n_m > 0) {
+        const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, n_m);
+        if (rc) return rc;
+    }
+    if (n == 0) return LC_OK;
+    AggParams P{};
+    P.W = 1;
+    P.n = n;
+    P.in_pos = vote_pos;
+    P.in_nz = vote_nz;
+    P.tie = -1;
+    P.theta = theta;
+    P.lr = lr;
+    P.wd = wd;
+    P.m = m;
+    P.m_stride = m_stride_elems;
+    P.g = g;
+    P.g_stride = g_stride_elems;
+    P.n_m = n_m;
+    P.beta2 = beta2;
+    P.omb2 = 1.0f - beta2;
+    return from_hip(launch_aggregate(P, 0, true, false, n_m > 0 ? g_dtype : LC_F32, static_cast<hipStream_t>(stream)));
+}
+
+int lc_momentum_avg(float *m, size_t m_stride_elems, int W, size_t n, void *stream)
+{
+    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    if (!m) return LC_ERR_NULL;
+    if (!aligned(m, 16) || (W > 1 && (m_stride_elems * 4) % 16 != 0)) return LC_ERR_ALIGN;
+    if (n == 0 || W == 1) return LC_OK;
+    return from_hip(launch_momentum_avg(m, m_stride_elems, W, n, static_cast<hipStream_t>(stream)));
+}
+
+int lc_container_bits(int p) { return container(p); }
+
+const char *lc_status_string(int status)
+{
+    switch (status) {
+    case LC_OK: return "LC_OK";
+    case LC_ERR_NULL: return "LC_ERR_NULL: a required pointer is NULL";
+    case LC_ERR_SIZE: return "LC_ERR_SIZE: worker count out of range";
+    case LC_ERR_ALIGN: return "LC_ERR_ALIGN: pointer or row stride misaligned";
+    case LC_ERR_RANGE: return "LC_ERR_RANGE: p outside 1..8 or W > 2^p - 1";
+    case LC_ERR_DTYPE: return "LC_ERR_DTYPE: unknown gradient dtype";
+    case LC_ERR_MODE: return "LC_ERR_MODE: unknown rule or bit width";
+    default: return status < 0 ? "HIP runtime error (status = -hipError_t)" : "unknown status";
+    }
+}
+
+int lc_version(void) { return 100; }
+
+}  // extern "C"

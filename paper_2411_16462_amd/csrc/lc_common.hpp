@@ -1,0 +1,67 @@
+// Shared device helpers for the Lion Cub kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lioncub.h"
+
+namespace lc {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;  // 4 waves per workgroup
+constexpr int kWaves = kBlock / kWave;
+
+using f32x4 = __attribute__((ext_vector_type(4))) float;
+using u32x4 = __attribute__((ext_vector_type(4))) uint32_t;
+using u32x2 = __attribute__((ext_vector_type(2))) uint32_t;
+
+__device__ __forceinline__ float bits_f32(uint32_t b) { return __uint_as_float(b); }
+
+// Gradient rows are fp32 or bfloat16; a bfloat16 is the upper half of a binary32, so
+// widening is a shift (exact).
+template <int GDT>
+struct Grad;
+
+template <>
+struct Grad<LC_F32> {
+    static constexpr int kBytes = 4;
+    static __device__ __forceinline__ f32x4 load4(const void *row, size_t i)
+    {
+        return *reinterpret_cast<const f32x4 *>(static_cast<const float *>(row) + i);
+    }
+    static __device__ __forceinline__ float load1(const void *row, size_t i)
+    {
+        return static_cast<const float *>(row)[i];
+    }
+};
+
+template <>
+struct Grad<LC_BF16> {
+    static constexpr int kBytes = 2;
+    static __device__ __forceinline__ f32x4 load4(const void *row, size_t i)
+    {
+        const u32x2 v = *reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(row) + i);
+        f32x4 r;
+        r.x = bits_f32(v.x << 16);
+        r.y = bits_f32(v.x & 0xffff0000u);
+        r.z = bits_f32(v.y << 16);
+        r.w = bits_f32(v.y & 0xffff0000u);
+        return r;
+    }
+    static __device__ __forceinline__ float load1(const void *row, size_t i)
+    {
+        return bits_f32(static_cast<uint32_t>(static_cast<const uint16_t *>(row)[i]) << 16);
+    }
+};
+
+__device__ __forceinline__ f32x4 load4(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+__device__ __forceinline__ void store4(float *p, f32x4 v) { *reinterpret_cast<f32x4 *>(p) = v; }
+
+// Algorithm 1 line 6 in fp32: one rounded product, one fused multiply-add.
+__device__ __forceinline__ float momentum_step(float m, float g, float beta2, float omb2)
+{
+    return __builtin_fmaf(beta2, m, omb2 * g);
+}
+
+}  // namespace lc

@@ -1,0 +1,39 @@
+// Host-side launchers of the kernel files and the parameter block of the aggregation
+// kernels.  Arguments are validated by the C-ABI layer before any of these is called.
+#pragma once
+
+#include "lc_common.hpp"
+
+namespace lc {
+
+struct AggParams {
+    const void *q;          // packed rows (1-bit words or fields); unused for IN_PLANES
+    size_t q_stride_bytes;
+    int W;
+    size_t n;
+    int sum_bits;           // container width of sum_out fields
+    void *sum_out;          // may be null
+    uint64_t *vote_pos;     // may be null
+    uint64_t *vote_nz;      // may be null
+    const uint64_t *in_pos; // IN_PLANES only
+    const uint64_t *in_nz;  // IN_PLANES only; null = every element non-zero
+    int tie;                // -1: tie -> 0 ; 0: tie -> -1 ; +1: tie -> +1
+    float *theta;
+    float lr, wd;
+    float *m;
+    size_t m_stride;
+    const void *g;
+    size_t g_stride;
+    int n_m;
+    float beta2, omb2;
+};
+
+hipError_t launch_local_update_pack(const void *g, size_t g_stride, int g_dtype, float *m, size_t m_stride, int W, size_t n,
+                                    float beta1, bool update_m, float beta2, int out_bits, void *q, size_t q_stride_bytes,
+                                    int zero_bit, hipStream_t s);
+// in_kind: 0 = vote planes, 1 = 1-bit rows, 2 / 4 / 8 = field rows of that width.
+// kout: the counts K are wanted as fields from 1-bit rows.
+hipError_t launch_aggregate(const AggParams &P, int in_kind, bool apply, bool kout, int g_dtype, hipStream_t s);
+hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStream_t s);
+
+}  // namespace lc

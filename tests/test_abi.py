@@ -1,0 +1,141 @@
+"""The C-ABI library loads, exports every symbol include/lioncub.h declares, and its
+host-side validation returns the documented status codes before anything is launched.
+No GPU needed: no call here reaches a kernel launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2411_16462_amd as lc
+from conftest import ROOT
+
+HEADER = os.path.join(ROOT, "include", "lioncub.h")
+A = 0x7F0000001000  # a 4 KiB-aligned address that is never dereferenced on the host
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported_and_bound():
+    names = declared_functions()
+    assert {"lc_local_update_pack", "lc_vote_1bit", "lc_pbit_sum_sign", "lc_apply_update",
+            "lc_momentum_avg"} <= set(names)
+    raw = ctypes.CDLL(lc.LIB_PATH)
+    for name in names:
+        assert hasattr(raw, name), "library does not export " + name
+        assert name in lc.SIGNATURES, "binding does not cover " + name
+        assert callable(getattr(lc, name))
+    assert set(lc.SIGNATURES) == set(names)
+
+
+def test_binding_constants_match_header():
+    text = open(HEADER).read()
+    for name in ("LC_OK", "LC_ERR_NULL", "LC_ERR_SIZE", "LC_ERR_ALIGN", "LC_ERR_RANGE", "LC_ERR_DTYPE",
+                 "LC_ERR_MODE", "LC_F32", "LC_BF16", "LC_ZERO_ALT", "LC_ZERO_POS", "LC_ZERO_NEG",
+                 "LC_TIE_ZERO", "LC_TIE_ALT"):
+        m = re.search(r"\b%s\s*=\s*(\d+)" % name, text)
+        assert m and int(m.group(1)) == getattr(lc, name), name
+    assert int(re.search(r"#define LC_MAX_W (\d+)", text).group(1)) == lc.LC_MAX_W
+
+
+def test_version_status_strings_and_container_rule():
+    assert lc.lc_version() >= 100
+    for code in range(0, 7):
+        assert lc.lc_status_string(code).startswith("LC_")
+    assert "HIP" in lc.lc_status_string(-1)
+    assert [lc.lc_container_bits(p) for p in range(0, 10)] == [-1, 1, 2, 4, 4, 8, 8, 8, 8, -1]
+
+
+def pack(**kw):
+    a = dict(g=A, g_stride_elems=1024, g_dtype=lc.LC_F32, m=A, m_stride_elems=1024, W=4, n=1000, beta1=0.9,
+             update_m=1, beta2=0.99, out_bits=1, q=A, q_stride_bytes=128, step=1, zero_rule=lc.LC_ZERO_ALT,
+             stream=0, check=False)
+    a.update(kw)
+    return lc.lc_local_update_pack(**a)
+
+
+def test_update_pack_validation():
+    assert pack(n=0) == lc.LC_OK                               # empty range: successful no-op
+    assert pack(W=0) == lc.LC_ERR_SIZE
+    assert pack(W=lc.LC_MAX_W + 1) == lc.LC_ERR_SIZE
+    assert pack(g=None) == lc.LC_ERR_NULL
+    assert pack(m=None) == lc.LC_ERR_NULL
+    assert pack(q=None, update_m=0) == lc.LC_ERR_NULL
+    assert pack(q=None, update_m=1, n=0) == lc.LC_OK
+    assert pack(g_dtype=2) == lc.LC_ERR_DTYPE
+    assert pack(out_bits=3) == lc.LC_ERR_MODE
+    assert pack(out_bits=16) == lc.LC_ERR_MODE
+    assert pack(zero_rule=3) == lc.LC_ERR_MODE
+    assert pack(m=A + 4) == lc.LC_ERR_ALIGN
+    assert pack(g=A + 8) == lc.LC_ERR_ALIGN
+    assert pack(m_stride_elems=1001) == lc.LC_ERR_ALIGN
+    assert pack(g_stride_elems=1004, g_dtype=lc.LC_BF16) == lc.LC_ERR_ALIGN   # 2008 bytes
+    assert pack(g_stride_elems=1001, W=1, n=0) == lc.LC_OK                     # one row: stride unused
+    assert pack(q=A + 4) == lc.LC_ERR_ALIGN
+    assert pack(q_stride_bytes=12) == lc.LC_ERR_ALIGN
+    assert pack(out_bits=4, q=A + 8) == lc.LC_ERR_ALIGN                        # field rows: 16 bytes
+    with pytest.raises(lc.LionCubError) as e:
+        pack(W=0, check=True)
+    assert e.value.status == lc.LC_ERR_SIZE
+
+
+def test_vote_and_sum_validation():
+    v = dict(q=A, q_stride_words=16, W=4, n=0, vote_pos=A, vote_nz=A, step=1, tie_rule=lc.LC_TIE_ZERO,
+             stream=0, check=False)
+    assert lc.lc_vote_1bit(**v) == lc.LC_OK
+    assert lc.lc_vote_1bit(**{**v, "W": 256}) == lc.LC_ERR_SIZE
+    assert lc.lc_vote_1bit(**{**v, "q": None}) == lc.LC_ERR_NULL
+    assert lc.lc_vote_1bit(**{**v, "tie_rule": 2}) == lc.LC_ERR_MODE
+    assert lc.lc_vote_1bit(**{**v, "q": A + 4}) == lc.LC_ERR_ALIGN
+    assert lc.lc_vote_1bit(**{**v, "vote_pos": A + 4}) == lc.LC_ERR_ALIGN
+    s = dict(q=A, q_stride_bytes=512, in_bits=4, W=8, n=0, p=4, sum_out=A, vote_pos=None, vote_nz=None,
+             step=1, tie_rule=lc.LC_TIE_ZERO, stream=0, check=False)
+    assert lc.lc_pbit_sum_sign(**s) == lc.LC_OK
+    # range rule of the p-bit sum: W <= 2^p - 1 (four bits cannot serve sixteen workers)
+    assert lc.lc_pbit_sum_sign(**{**s, "W": 15}) == lc.LC_OK
+    assert lc.lc_pbit_sum_sign(**{**s, "W": 16}) == lc.LC_ERR_RANGE
+    assert lc.lc_pbit_sum_sign(**{**s, "p": 3, "W": 7}) == lc.LC_OK         # 3 bits live in a nibble
+    assert lc.lc_pbit_sum_sign(**{**s, "p": 3, "W": 8}) == lc.LC_ERR_RANGE
+    assert lc.lc_pbit_sum_sign(**{**s, "p": 7, "in_bits": 1, "W": 64}) == lc.LC_OK
+    assert lc.lc_pbit_sum_sign(**{**s, "p": 6, "in_bits": 1, "W": 64}) == lc.LC_ERR_RANGE
+    assert lc.lc_pbit_sum_sign(**{**s, "p": 8, "in_bits": 8, "W": 125}) == lc.LC_OK
+    assert lc.lc_pbit_sum_sign(**{**s, "p": 0}) == lc.LC_ERR_RANGE
+    assert lc.lc_pbit_sum_sign(**{**s, "p": 9}) == lc.LC_ERR_RANGE
+    assert lc.lc_pbit_sum_sign(**{**s, "in_bits": 2}) == lc.LC_ERR_MODE       # must be 1 or container(p)
+    assert lc.lc_pbit_sum_sign(**{**s, "q": A + 8}) == lc.LC_ERR_ALIGN
+    assert lc.lc_pbit_sum_sign(**{**s, "q_stride_bytes": 520}) == lc.LC_ERR_ALIGN
+    assert lc.lc_pbit_sum_sign(**{**s, "sum_out": A + 8}) == lc.LC_ERR_ALIGN
+
+
+def test_apply_avg_and_fused_validation():
+    a = dict(theta=A, vote_pos=A, vote_nz=A, n=0, lr=1e-4, wd=0.1, m=None, m_stride_elems=0, g=None,
+             g_stride_elems=0, g_dtype=lc.LC_F32, n_m=0, beta2=0.99, stream=0, check=False)
+    assert lc.lc_apply_update(**a) == lc.LC_OK
+    assert lc.lc_apply_update(**{**a, "vote_nz": None}) == lc.LC_OK           # one-plane update
+    assert lc.lc_apply_update(**{**a, "theta": None}) == lc.LC_ERR_NULL
+    assert lc.lc_apply_update(**{**a, "vote_pos": None}) == lc.LC_ERR_NULL
+    assert lc.lc_apply_update(**{**a, "theta": A + 4}) == lc.LC_ERR_ALIGN
+    assert lc.lc_apply_update(**{**a, "n_m": 1}) == lc.LC_ERR_NULL            # needs m and g
+    assert lc.lc_apply_update(**{**a, "n_m": -1}) == lc.LC_ERR_SIZE
+    assert lc.lc_apply_update(**{**a, "n_m": 1, "m": A, "g": A, "g_dtype": 7}) == lc.LC_ERR_DTYPE
+    assert lc.lc_momentum_avg(A, 1024, 4, 0, stream=0, check=False) == lc.LC_OK
+    assert lc.lc_momentum_avg(None, 1024, 4, 10, stream=0, check=False) == lc.LC_ERR_NULL
+    assert lc.lc_momentum_avg(A, 1023, 4, 10, stream=0, check=False) == lc.LC_ERR_ALIGN
+    assert lc.lc_momentum_avg(A, 1024, 0, 10, stream=0, check=False) == lc.LC_ERR_SIZE
+    assert lc.lc_momentum_avg(A, 1023, 1, 10, stream=0, check=False) == lc.LC_OK   # W = 1: nothing to do
+    f = dict(q=A, q_stride_words=16, W=4, n=0, step=1, tie_rule=lc.LC_TIE_ZERO, theta=A, lr=1e-4, wd=0.1,
+             m=None, m_stride_elems=0, g=None, g_stride_elems=0, g_dtype=lc.LC_F32, n_m=0, beta2=0.99,
+             stream=0, check=False)
+    assert lc.lc_vote_apply_1bit(**f) == lc.LC_OK
+    assert lc.lc_vote_apply_1bit(**{**f, "theta": None}) == lc.LC_ERR_NULL
+    assert lc.lc_vote_apply_1bit(**{**f, "n_m": 2}) == lc.LC_ERR_NULL
+    pa = dict(q=A, q_stride_bytes=512, in_bits=4, W=8, n=0, p=4, sum_out=None, step=1,
+              tie_rule=lc.LC_TIE_ZERO, theta=A, lr=1e-4, wd=0.1, m=None, m_stride_elems=0, g=None,
+              g_stride_elems=0, g_dtype=lc.LC_F32, n_m=0, beta2=0.99, stream=0, check=False)
+    assert lc.lc_pbit_sum_apply(**pa) == lc.LC_OK
+    assert lc.lc_pbit_sum_apply(**{**pa, "W": 16}) == lc.LC_ERR_RANGE
+    assert lc.lc_pbit_sum_apply(**{**pa, "theta": None}) == lc.LC_ERR_NULL

@@ -1,0 +1,260 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs -- bit-exact for signs, packed words, fields, counts and votes; within
+1e-6 relative / 1e-7 absolute for updated parameters and momenta."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import paper_2411_16462_amd as lc
+from harness import (SENTINEL, Case, assert_close, guarded, hip_update_pack, oracle_step, untouched, words_of)
+
+pytestmark = pytest.mark.gpu
+
+HP = dict(beta1=0.9, beta2=0.99, lr=1e-4, wd=0.1)
+SIZES = [1, 63, 64, 65, 1000, 1023, 1024, 1025, 4095, 4096, 4097, 16384 + 17, 3 * 16384]
+
+
+def nwords(n):
+    return (n + 63) // 64
+
+
+def run_1bit(case, step, zero=lc.LC_ZERO_ALT, tie=lc.LC_TIE_ZERO, fused=True, hp=HP):
+    """update+pack, then vote (+apply).  Returns every stage as numpy."""
+    n, W = case.n, case.W
+    nw = nwords(n)
+    q, nbytes = hip_update_pack(case, hp, step, 1, zero)
+    out = dict(words=words_of(q, nw), q_clean=untouched(q, nbytes), m=case.m.cpu().numpy())
+    pos = guarded(1, nw * 8, case.device)
+    nz = guarded(1, nw * 8, case.device)
+    lc.lc_vote_1bit(q, q.stride(0) // 8, W, n, pos, nz, step, tie)
+    out["pos"], out["nz"] = words_of(pos, nw)[0], words_of(nz, nw)[0]
+    out["planes_clean"] = untouched(pos, nw * 8) and untouched(nz, nw * 8)
+    if fused:
+        lc.lc_vote_apply_1bit(q, q.stride(0) // 8, W, n, step, tie, case.theta, hp["lr"], hp["wd"], None, 0, None, 0,
+                              lc.LC_F32, 0, hp["beta2"])
+    else:
+        lc.lc_apply_update(case.theta, pos, nz, n, hp["lr"], hp["wd"], None, 0, None, 0, lc.LC_F32, 0, hp["beta2"])
+    torch.cuda.synchronize()
+    out["theta"] = case.theta.cpu().numpy()
+    return out
+
+
+def check_1bit(out, ref):
+    assert np.array_equal(out["words"], ref["words"]), "packed sign words"
+    assert out["q_clean"] and out["planes_clean"], "wrote past the end of a packed row"
+    assert np.array_equal(out["pos"], ref["pos"]), "vote plane pos"
+    assert np.array_equal(out["nz"], ref["nz"]), "vote plane nz"
+    assert_close(out["m"], ref["m"], "momentum")
+    assert_close(out["theta"], ref["theta"], "theta")
+
+
+@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("W", [1, 4, 7])
+def test_1bit_sizes(n, W):
+    for step, fused in ((1, True), (2, False)):
+        case = Case(n, W, seed=1000 + n + W, m_spread=1.0)
+        out = run_1bit(case, step, fused=fused)
+        check_1bit(out, oracle_step(case, HP, step))
+
+
+@pytest.mark.parametrize("W", [2, 3, 8, 9, 15, 16, 17, 31, 64, 65, 127, 128, 255])
+def test_1bit_worker_counts(W):
+    n = 4096 + 333
+    case = Case(n, W, seed=2000 + W, m_scale=0.0)          # m = 0: signs nearly independent -> many ties
+    out = run_1bit(case, step=1)
+    ref = oracle_step(case, HP, 1)
+    check_1bit(out, ref)
+    if W % 2 == 0 and W <= 16:
+        assert (ref["u"] == 0).mean() > 0.05                # ties really occur in this case
+
+
+@pytest.mark.parametrize("g_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("zero", [lc.LC_ZERO_ALT, lc.LC_ZERO_POS, lc.LC_ZERO_NEG])
+@pytest.mark.parametrize("tie", [lc.LC_TIE_ZERO, lc.LC_TIE_ALT])
+@pytest.mark.parametrize("step", [1, 2])
+def test_1bit_rules_and_dtypes(g_dtype, zero, tie, step):
+    n, W = 20000, 4
+    case = Case(n, W, seed=3000, g_dtype=g_dtype, m_scale=0.0)
+    # exact zeros of c: whole columns (all workers) and single workers
+    case.g[:, 100:300] = 0
+    case.g[1, 5000:5100] = 0
+    case.g[:, n - 7:] = 0
+    case.snapshot()
+    out = run_1bit(case, step, zero, tie)
+    ref = oracle_step(case, HP, step, zero, tie)
+    assert (ref["s"][:, 100:300] == 0).all()
+    check_1bit(out, ref)
+
+
+def test_special_values():
+    """NaN, infinities, signed zeros, denormals and exact cancellation in c."""
+    n, W = 4096 + 64, 3
+    case = Case(n, W, seed=4000)
+    tiny = 2.0 ** -148
+    vals_m = torch.tensor([0.0, -0.0, float("nan"), float("inf"), -float("inf"), tiny, -tiny, 1.0, 1e-38, -1e-38])
+    vals_g = torch.tensor([0.0, -0.0, 1.0, 1.0, 1.0, 0.0, 0.0, -9.0, -1e-38, 1e-38])
+    k = vals_m.numel()
+    for base in (0, 4096):                     # once in the vector path, once in the ragged tail
+        case.m[:, base:base + k] = vals_m.to(case.m.device)
+        case.g[:, base:base + k] = vals_g.to(case.g.device)
+    case.snapshot()
+    hp = dict(HP, beta1=0.5)
+    n_w = nwords(n)
+    for step in (1, 2):
+        q, nbytes = hip_update_pack(case, hp, step, 1, update_m=False)
+        ref = oracle_step(case, hp, step)
+        assert ref["s"][0, :8].tolist() == [0, 0, 0, 1, -1, 1, -1, -1]
+        assert np.array_equal(words_of(q, n_w), ref["words"])
+
+
+def test_update_without_q_and_pack_without_update():
+    n, W = 10000, 3
+    case = Case(n, W, seed=5000)
+    ref = oracle_step(case, HP, 1)
+    q, nbytes = hip_update_pack(case, HP, 1, 1, update_m=False)
+    assert np.array_equal(words_of(q, nwords(n)), ref["words"])
+    assert np.array_equal(case.m.cpu().numpy(), case.m0)          # momentum untouched
+    hip_update_pack(case, HP, 1, 1, want_q=False)
+    assert_close(case.m.cpu().numpy(), ref["m"], "momentum")
+
+
+@pytest.mark.parametrize("p,W", [(1, 1), (2, 3), (3, 7), (4, 8), (4, 15), (5, 16), (7, 64), (8, 125), (8, 255)])
+@pytest.mark.parametrize("n", [1, 31, 1000, 2048 + 5, 4096, 16384 + 17])
+def test_pbit_fields(p, W, n):
+    C = lc.lc_container_bits(p)
+    step = 1 + (n % 2)
+    case = Case(n, W, seed=6000 + p * 1000 + n, m_scale=0.0, noise=0.5)
+    case.g[:, : min(n, 40)] = 0
+    case.snapshot()
+    ref = oracle_step(case, HP, step, p=p)
+    q, nbytes = hip_update_pack(case, HP, step, C)
+    if C == 1:
+        got_fields = q[:, : nbytes].cpu().numpy()[:, : (n + 7) // 8]
+    else:
+        got_fields = q[:, : nbytes].cpu().numpy()
+    assert np.array_equal(got_fields, ref["fields"]), "p-bit fields"
+    assert untouched(q, nbytes)
+    assert_close(case.m.cpu().numpy(), ref["m"], "momentum")
+    nw = nwords(n)
+    fb = (n * C + 7) // 8
+    sum_out = guarded(1, nw * 8 if C == 1 else fb, case.device)
+    pos, nz = guarded(1, nw * 8, case.device), guarded(1, nw * 8, case.device)
+    lc.lc_pbit_sum_sign(q, q.stride(0), C, W, n, p, sum_out, pos, nz, step, lc.LC_TIE_ZERO)
+    torch.cuda.synchronize()
+    assert np.array_equal(sum_out[0, :fb].cpu().numpy(), ref["sum_fields"]), "field sums"
+    assert untouched(sum_out, nw * 8 if C == 1 else fb)
+    assert np.array_equal(words_of(pos, nw)[0], ref["pos"]) and np.array_equal(words_of(nz, nw)[0], ref["nz"])
+    sum2 = guarded(1, nw * 8 if C == 1 else fb, case.device)
+    lc.lc_pbit_sum_apply(q, q.stride(0), C, W, n, p, sum2, step, lc.LC_TIE_ZERO, case.theta, HP["lr"], HP["wd"],
+                         None, 0, None, 0, lc.LC_F32, 0, HP["beta2"])
+    torch.cuda.synchronize()
+    assert np.array_equal(sum2[0, :fb].cpu().numpy(), ref["sum_fields"])
+    assert_close(case.theta.cpu().numpy(), ref["theta"], "theta")
+
+
+@pytest.mark.parametrize("p,W", [(2, 3), (4, 8), (4, 15), (7, 64), (8, 200)])
+@pytest.mark.parametrize("n", [5, 4096 + 3, 16384 * 2 + 100])
+def test_pbit_sum_from_1bit_rows(p, W, n):
+    """The counts K as p-bit fields computed from 1-bit buffers (the form of the
+    reduction-only workload), fused with apply and a one-stream momentum update."""
+    C = lc.lc_container_bits(p)
+    case = Case(n, W, seed=7000 + p + n, m_scale=0.0)
+    ref = oracle_step(case, HP, 2, tie=orc.TIE_ALT, p=p)
+    q, nbytes = hip_update_pack(case, HP, 2, 1, update_m=False)
+    fb = (n * C + 7) // 8
+    nw = nwords(n)
+    s1, s2 = guarded(1, fb, case.device), guarded(1, fb, case.device)
+    pos, nz = guarded(1, nw * 8, case.device), guarded(1, nw * 8, case.device)
+    lc.lc_pbit_sum_sign(q, q.stride(0), 1, W, n, p, s1, pos, nz, 2, lc.LC_TIE_ALT)
+    lc.lc_pbit_sum_apply(q, q.stride(0), 1, W, n, p, s2, 2, lc.LC_TIE_ALT, case.theta, HP["lr"], HP["wd"],
+                         case.m, case.m.stride(0), case.g, case.g.stride(0), lc.LC_F32, 1, HP["beta2"])
+    torch.cuda.synchronize()
+    for s in (s1, s2):
+        assert np.array_equal(s[0, :fb].cpu().numpy(), ref["sum_fields"]), "counts from 1-bit rows"
+        assert untouched(s, fb)
+    assert np.array_equal(words_of(pos, nw)[0], ref["pos"]) and np.array_equal(words_of(nz, nw)[0], ref["nz"])
+    assert (words_of(nz, nw)[0][:-1] == np.uint64(2 ** 64 - 1)).all()         # TIE_ALT leaves no zero
+    assert_close(case.theta.cpu().numpy(), ref["theta"], "theta")
+    m = case.m.cpu().numpy()
+    assert_close(m[0], ref["m"][0], "momentum of stream 0")
+    assert np.array_equal(m[1:], case.m0[1:])                                  # n_m = 1: others untouched
+
+
+@pytest.mark.parametrize("g_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n_m", [1, 3])
+@pytest.mark.parametrize("n", [777, 16384 + 4099])
+def test_apply_with_momentum_streams(g_dtype, n_m, n):
+    """lc_apply_update / lc_vote_apply_1bit with the momentum update done in the apply pass."""
+    W = 4
+    case = Case(n, W, seed=8000 + n, g_dtype=g_dtype, m_scale=0.0)
+    ref = oracle_step(case, HP, 1)
+    q, _ = hip_update_pack(case, HP, 1, 1, update_m=False)
+    theta_a = case.theta.clone()
+    m_a = case.m.clone()
+    lc.lc_vote_apply_1bit(q, q.stride(0) // 8, W, n, 1, lc.LC_TIE_ZERO, case.theta, HP["lr"], HP["wd"], case.m,
+                          case.m.stride(0), case.g, case.g.stride(0), case.gd, n_m, HP["beta2"])
+    nw = nwords(n)
+    pos, nz = guarded(1, nw * 8, case.device), guarded(1, nw * 8, case.device)
+    lc.lc_vote_1bit(q, q.stride(0) // 8, W, n, pos, nz, 1, lc.LC_TIE_ZERO)
+    lc.lc_apply_update(theta_a, pos, nz, n, HP["lr"], HP["wd"], m_a, m_a.stride(0), case.g, case.g.stride(0), case.gd,
+                       n_m, HP["beta2"])
+    torch.cuda.synchronize()
+    for th, mm in ((case.theta, case.m), (theta_a, m_a)):
+        assert_close(th.cpu().numpy(), ref["theta"], "theta")
+        got = mm.cpu().numpy()
+        assert_close(got[:n_m], ref["m"][:n_m], "momentum")
+        assert np.array_equal(got[n_m:], case.m0[n_m:])
+    assert torch.equal(theta_a, case.theta) and torch.equal(m_a, case.m)      # fused == unfused, bit for bit
+
+
+def test_apply_one_plane():
+    """vote_nz = NULL: every element moves, -1 where the pos bit is clear."""
+    n, W = 5000, 4
+    case = Case(n, W, seed=8500, m_scale=0.0)
+    ref = oracle_step(case, HP, 1, tie=orc.TIE_ALT)
+    q, _ = hip_update_pack(case, HP, 1, 1, update_m=False)
+    nw = nwords(n)
+    pos = guarded(1, nw * 8, case.device)
+    lc.lc_vote_1bit(q, q.stride(0) // 8, W, n, pos, None, 1, lc.LC_TIE_ALT)
+    lc.lc_apply_update(case.theta, pos, None, n, HP["lr"], HP["wd"], None, 0, None, 0, lc.LC_F32, 0, HP["beta2"])
+    torch.cuda.synchronize()
+    assert_close(case.theta.cpu().numpy(), ref["theta"], "theta")
+
+
+@pytest.mark.parametrize("W", [2, 3, 8, 16, 33])
+@pytest.mark.parametrize("n", [1, 3, 4, 1023, 1024, 1025, 70001])
+def test_momentum_avg(W, n):
+    case = Case(n, W, seed=9000 + W + n, m_spread=1.0)
+    ref = orc.momentum_avg(case.m0)
+    lc.lc_momentum_avg(case.m, case.m.stride(0), W, n)
+    torch.cuda.synchronize()
+    got = case.m.cpu().numpy()
+    for w in range(W):
+        assert_close(got[w], ref, "averaged momentum row %d" % w)
+    assert (got == got[0]).all()
+
+
+def test_empty_range_is_a_noop():
+    case = Case(64, 2, seed=1)
+    q = guarded(2, 8, case.device)
+    lc.lc_local_update_pack(case.g, case.g.stride(0), case.gd, case.m, case.m.stride(0), 2, 0, 0.9, 1, 0.99, 1, q,
+                            q.stride(0), 1, lc.LC_ZERO_ALT)
+    lc.lc_vote_apply_1bit(q, q.stride(0) // 8, 2, 0, 1, lc.LC_TIE_ZERO, case.theta, 1e-4, 0.1, None, 0, None, 0,
+                          lc.LC_F32, 0, 0.99)
+    lc.lc_momentum_avg(case.m, case.m.stride(0), 2, 0)
+    torch.cuda.synchronize()
+    assert (q == SENTINEL).all().item()
+    assert np.array_equal(case.m.cpu().numpy(), case.m0) and np.array_equal(case.theta.cpu().numpy(), case.theta0)
+
+
+def test_multi_step_trajectory():
+    """Four consecutive steps (odd and even iterations) with state carried on the GPU;
+    the oracle restarts each step from the GPU's fp32 state, so errors cannot hide in drift."""
+    n, W = 50000, 4
+    case = Case(n, W, seed=10000)
+    for step in range(1, 5):
+        case.g.copy_(torch.randn(W, n, generator=torch.Generator(device="cuda").manual_seed(step), device="cuda") * 1e-3)
+        case.snapshot()
+        out = run_1bit(case, step)
+        check_1bit(out, oracle_step(case, HP, step))
