@@ -42,6 +42,15 @@ def guarded(rows, nbytes, device, align=64):
     return torch.full((rows, stride), SENTINEL, dtype=torch.uint8, device=device)
 
 
+def clone_rows(t):
+    """Copy of a (W, n) row buffer that keeps the rows aligned (a plain clone() of the
+    view would pack the rows back to back)."""
+    out = torch.zeros((t.shape[0], synth.round_up(max(t.shape[1], 1), synth.ROW_ALIGN)), dtype=t.dtype,
+                      device=t.device)[:, : t.shape[1]]
+    out.copy_(t)
+    return out
+
+
 def words_of(buf, nw):
     """First nw 64-bit words of every row of a guarded uint8 buffer, as uint64 numpy."""
     return buf[:, : nw * 8].contiguous().cpu().numpy().view(np.uint64)

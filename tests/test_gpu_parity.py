@@ -7,7 +7,7 @@ import torch
 
 import oracle as orc
 import paper_2411_16462_amd as lc
-from harness import (SENTINEL, Case, assert_close, guarded, hip_update_pack, oracle_step, untouched, words_of)
+from harness import (SENTINEL, Case, assert_close, clone_rows, guarded, hip_update_pack, oracle_step, untouched, words_of)
 
 pytestmark = pytest.mark.gpu
 
@@ -191,7 +191,7 @@ def test_apply_with_momentum_streams(g_dtype, n_m, n):
     ref = oracle_step(case, HP, 1)
     q, _ = hip_update_pack(case, HP, 1, 1, update_m=False)
     theta_a = case.theta.clone()
-    m_a = case.m.clone()
+    m_a = clone_rows(case.m)
     lc.lc_vote_apply_1bit(q, q.stride(0) // 8, W, n, 1, lc.LC_TIE_ZERO, case.theta, HP["lr"], HP["wd"], case.m,
                           case.m.stride(0), case.g, case.g.stride(0), case.gd, n_m, HP["beta2"])
     nw = nwords(n)
