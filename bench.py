@@ -30,6 +30,9 @@ def parse():
     ap.add_argument("--workload", default="c1")
     ap.add_argument("--cpu-sample", type=int, default=1 << 25, help="parameters in the oracle's sample (0: skip)")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = host cores available, capped at 16")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
+                    help="also run one plain device copy of BYTES (read BYTES, write BYTES) before the steps: "
+                         "the reference point for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
 
 
@@ -193,6 +196,13 @@ def main():
     wl = synth.workload(args.workload)
     kernels, st, step_no = build_step(wl, torch, lc, synth)
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        src = torch.empty(args.copy_calibration, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def one_step(timed):
         for k in kernels:

@@ -2,34 +2,45 @@
 // apply step, as one kernel family (Algorithm 1 lines 4-6; Section 3; Appendix A.1, B.1
 // and F.1).
 //
-// A wave owns kAggWave = 4096 consecutive elements (64 packed words) and runs three phases:
+// Every wave works alone on kAggWave = 1024 consecutive elements (16 packed words, four
+// 256-element tiles) and is short-lived: on MI355X many small independent waves stream
+// faster than few long ones.  Three phases:
 //
-//  A  count   Lanes own packed input.  1-bit rows: lane j holds word j of every worker
-//             and counts bit-sliced: carry-save adders fold 8 words at a time into
-//             planes c[0..7] (c[k] bit i = bit k of K_i), about 6 bitwise ops per word
-//             for 64 elements.  K is compared with W/2 bit-sliced as well, giving the
-//             `pos` (S > 0) and `nz` (S != 0) words directly.  Field rows: lane holds 16
-//             bytes of fields per worker and adds them as four 32-bit integers -- no
-//             carry crosses a field because K <= W <= 2^p - 1 -- then compares field
-//             by field.
+//  A  count   1-bit rows: lane = 16 * phase + j.  Lane (phase, j) loads word j of rows
+//             phase, phase + 4, phase + 8, ... (one load instruction fetches 128
+//             contiguous bytes from each of 4 rows) and counts them bit-sliced:
+//             carry-save adders fold 8 words at a time into planes c[0..7]
+//             (c[k] bit i = bit k of the count for element i).  Two butterfly steps
+//             over the lane pairs 16 and 32 apart add the four partial counts, also
+//             bit-sliced.  K is compared with W/2 plane by plane, giving the `pos`
+//             (S > 0) and `nz` (S != 0) words directly.
+//             Field rows: a lane owns 16 consecutive fields of every row (4, 8 or 16
+//             bytes) and adds the rows as 32-bit integers -- no carry crosses a field
+//             because K <= W <= 2^p - 1 -- then compares field by field.
 //  B  stage   pos / nz (and, if the counts K are wanted from 1-bit rows, the count
-//             planes) go to LDS in the canonical 1-bit layout; the planes are also
-//             stored to global memory if the caller asked for them.
-//  C  apply   Lanes own elements: tile t, lane l holds elements 256 t + 4 l .. + 3
+//             planes) go to the wave's slice of LDS in the canonical 1-bit layout;
+//             the planes are also stored to global memory if the caller asked.
+//  C  apply   Lanes own elements: in tile t lane l holds elements 256 t + 4 l .. + 3
 //             (16-byte accesses of theta, m, g) and fetches its 4 pos / nz bits from
-//             LDS.  This is the only place where the word-per-lane and element-per-lane
-//             layouts meet, and the only use of LDS.
+//             LDS.  This is the only place where the word-per-lane and the
+//             element-per-lane layouts meet, and the only use of LDS.  The loads of
+//             theta are issued before phase A so that they overlap the counting.
 #include "lc_launch.hpp"
 
 namespace lc {
 
-constexpr int kAggWords = 64;                 // packed words per wave
+#ifndef LC_AGG_THREADS
+#define LC_AGG_THREADS 64
+#endif
+constexpr int kAggThreads = LC_AGG_THREADS;   // workgroup size; waves are independent
+constexpr int kWaves = kAggThreads / kWave;
+constexpr int kAggWords = 16;                 // packed words per wave
 constexpr int kAggWave = kAggWords * 64;      // elements per wave
 constexpr int kAggBlock = kAggWave * kWaves;  // elements per workgroup
 constexpr int kAggTiles = kAggWave / 256;
+constexpr int kPhases = kWave / kAggWords;    // lanes that share a word in phase A
 
 enum { IN_PLANES = 0, IN_BITS = 1 /* 2, 4, 8: field width */ };
-
 
 // a + b + c = 2 h + l, bitwise in every position
 __device__ __forceinline__ void csa(uint64_t &h, uint64_t &l, uint64_t a, uint64_t b, uint64_t c)
@@ -92,8 +103,73 @@ __device__ __forceinline__ uint32_t spread4(uint32_t nib)
     return (nib & 1u) | ((nib & 2u) << 7) | ((nib & 4u) << 14) | ((nib & 8u) << 21);
 }
 
+
+// LDS traffic of one wave is ordered by the hardware; this keeps the compiler from
+// moving the reads above the writes and waits for the writes to land.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+__device__ __forceinline__ uint64_t lane_xor64(uint64_t v, int lane, int mask)
+{
+    const int addr = (lane ^ mask) << 2;
+    const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(addr, static_cast<int>(static_cast<uint32_t>(v))));
+    const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(addr, static_cast<int>(static_cast<uint32_t>(v >> 32))));
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+// c += the planes of the lane `mask` away (bit-sliced ripple-carry add); np planes hold the total
+__device__ __forceinline__ void add_partner(uint64_t (&c)[8], int lane, int mask, int np)
+{
+    uint64_t carry = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        if (k >= np) break;
+        const uint64_t o = lane_xor64(c[k], lane, mask);
+        const uint64_t t = c[k] ^ o;
+        const uint64_t cy = (c[k] & o) | (t & carry);
+        c[k] = t ^ carry;
+        carry = cy;
+    }
+}
+
+template <int NWD>
+__device__ __forceinline__ void load_words(const char *p, uint32_t (&x)[NWD])
+{
+    if constexpr (NWD == 1) {
+        x[0] = ld_packed(reinterpret_cast<const uint32_t *>(p));
+    } else if constexpr (NWD == 2) {
+        const u32x2 v = ld_packed(reinterpret_cast<const u32x2 *>(p));
+        x[0] = v.x;
+        x[1] = v.y;
+    } else {
+        const u32x4 v = ld_packed(reinterpret_cast<const u32x4 *>(p));
+        x[0] = v.x;
+        x[1] = v.y;
+        x[2] = v.z;
+        x[3] = v.w;
+    }
+}
+
+template <int NWD>
+__device__ __forceinline__ void store_words(char *p, const uint32_t (&x)[NWD])
+{
+    if constexpr (NWD == 1) {
+        st_stream(reinterpret_cast<uint32_t *>(p), x[0]);
+    } else if constexpr (NWD == 2) {
+        u32x2 v = {x[0], x[1]};
+        st_stream(reinterpret_cast<u32x2 *>(p), v);
+    } else {
+        u32x4 v = {x[0], x[1], x[2], x[3]};
+        st_stream(reinterpret_cast<u32x4 *>(p), v);
+    }
+}
+
 template <int IN, int GDT, bool APPLY, bool KOUT>
-__global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggParams P)
+__global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams P)
 {
     __shared__ uint64_t s_pos[kWaves][kAggWords];
     __shared__ uint64_t s_nz[kWaves][kAggWords];
@@ -103,134 +179,149 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggParams P)
     const int wave = threadIdx.x / kWave;
     const size_t n = P.n;
     const size_t wave_base = (static_cast<size_t>(blockIdx.x) * kWaves + wave) * kAggWave;
-    const bool active = wave_base < n;
+    if (wave_base >= n) return;
+    const bool full_wave = wave_base + kAggWave <= n;
     const int W = P.W;
     const int T = W >> 1;
 
-    // ---------------------------------------------------------------- phase A + B
-    if (active) {
-        if constexpr (IN == IN_PLANES) {
-            const size_t jw = wave_base / 64 + lane;
-            const uint64_t vm = valid_mask(jw * 64, n);
-            uint64_t pos = 0, nz = 0;
-            if (vm) {
-                pos = P.in_pos[jw];
-                nz = P.in_nz ? P.in_nz[jw] : ~0ull;
-            }
-            s_pos[wave][lane] = pos & nz & vm;
-            s_nz[wave][lane] = nz & vm;
-        } else if constexpr (IN == IN_BITS) {
-            const size_t jw = wave_base / 64 + lane;
-            const uint64_t vm = valid_mask(jw * 64, n);
-            const size_t stride = P.q_stride_bytes / 8;
-            const uint64_t *qp = static_cast<const uint64_t *>(P.q) + jw;
-            uint64_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            int w = 0;
-            for (; w + 8 <= W; w += 8) {
-                uint64_t x[8];
+    // theta first: these loads overlap all of phase A
+    f32x4 th[kAggTiles];
+    if (APPLY && full_wave) {
 #pragma unroll
-                for (int k = 0; k < 8; ++k) x[k] = vm ? qp[static_cast<size_t>(w + k) * stride] : 0ull;
-                uint64_t ta, tb, fa, fb, e;
-                csa(ta, c[0], c[0], x[0], x[1]);
-                csa(tb, c[0], c[0], x[2], x[3]);
-                csa(fa, c[1], c[1], ta, tb);
-                csa(ta, c[0], c[0], x[4], x[5]);
-                csa(tb, c[0], c[0], x[6], x[7]);
-                csa(fb, c[1], c[1], ta, tb);
-                csa(e, c[2], c[2], fa, fb);
-                ripple(c, e, 3);
+        for (int t = 0; t < kAggTiles; ++t) th[t] = load4(P.theta + wave_base + t * 256 + lane * 4);
+    }
+
+    // ---------------------------------------------------------------- phase A + B
+    if constexpr (IN == IN_PLANES) {
+        if (lane < 2 * kAggWords) {
+            const int j = lane & (kAggWords - 1);
+            const size_t jw = wave_base / 64 + j;
+            const uint64_t vm = valid_mask(jw * 64, n);
+            uint64_t v = 0;
+            if (lane < kAggWords) {
+                if (vm) v = ld_packed(P.in_pos + jw);
+                s_pos[wave][j] = v & vm;
+            } else {
+                if (vm) v = P.in_nz ? ld_packed(P.in_nz + jw) : ~0ull;
+                s_nz[wave][j] = v & vm;
             }
-            for (; w < W; ++w) ripple(c, vm ? qp[static_cast<size_t>(w) * stride] : 0ull, 0);
-            uint64_t gt, eq, pos, nz;
-            compare_planes(c, T, gt, eq);
-            vote_planes(gt, eq, W, P.tie, pos, nz);
-            pos &= vm;
-            nz &= vm;
-            s_pos[wave][lane] = pos;
-            s_nz[wave][lane] = nz;
+        }
+    } else if constexpr (IN == IN_BITS) {
+        const int j = lane & (kAggWords - 1);
+        const int ph = lane / kAggWords;
+        const size_t jw = wave_base / 64 + j;
+        const uint64_t vm = valid_mask(jw * 64, n);
+        const size_t stride = P.q_stride_bytes / 8;
+        const uint64_t *qp = static_cast<const uint64_t *>(P.q) + jw + static_cast<size_t>(ph) * stride;
+        const size_t step4 = stride * kPhases;
+        const int np = 32 - __builtin_clz(static_cast<unsigned>(W));  // planes that hold a count up to W
+        uint64_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        const int every = W / kPhases;                 // rows that exist for every phase
+        const int most = (W + kPhases - 1) / kPhases;  // rows of phase 0
+        int k = 0;
+        for (; k + 8 <= every; k += 8) {
+            uint64_t x[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = vm ? ld_packed(qp + static_cast<size_t>(k + i) * step4) : 0ull;
+            uint64_t ta, tb, fa, fb, e;
+            csa(ta, c[0], c[0], x[0], x[1]);
+            csa(tb, c[0], c[0], x[2], x[3]);
+            csa(fa, c[1], c[1], ta, tb);
+            csa(ta, c[0], c[0], x[4], x[5]);
+            csa(tb, c[0], c[0], x[6], x[7]);
+            csa(fb, c[1], c[1], ta, tb);
+            csa(e, c[2], c[2], fa, fb);
+            ripple(c, e, 3);
+        }
+        for (; k < most; ++k) {
+            const bool have = vm && (ph + k * kPhases < W);
+            ripple(c, have ? ld_packed(qp + static_cast<size_t>(k) * step4) : 0ull, 0);
+        }
+        add_partner(c, lane, 16, np);
+        add_partner(c, lane, 32, np);
+        uint64_t gt, eq, pos, nz;
+        compare_planes(c, T, gt, eq);
+        vote_planes(gt, eq, W, P.tie, pos, nz);
+        pos &= vm;
+        nz &= vm;
+        if (ph == 0) {
+            s_pos[wave][j] = pos;
+            s_nz[wave][j] = nz;
             if (KOUT) {
 #pragma unroll
-                for (int k = 0; k < 8; ++k) s_cnt[KOUT ? wave : 0][KOUT ? k : 0][KOUT ? lane : 0] = c[k] & vm;
+                for (int i = 0; i < 8; ++i) s_cnt[KOUT ? wave : 0][KOUT ? i : 0][KOUT ? j : 0] = c[i] & vm;
                 if (P.sum_bits == 1 && vm) static_cast<uint64_t *>(P.sum_out)[jw] = c[0] & vm;  // W = 1: K is the bit
             }
             if (vm) {
                 if (P.vote_pos) P.vote_pos[jw] = pos;
                 if (P.vote_nz) P.vote_nz[jw] = nz;
             }
-        } else {
-            // field rows: lane owns 16 bytes = kFpl fields per round
-            constexpr int C = IN;
-            constexpr int kFpl = 128 / C;            // fields per lane per round
-            constexpr int kRound = kWave * kFpl;     // elements per round
-            constexpr int kRounds = kAggWave / kRound;
-            constexpr uint32_t fmask = (1u << C) - 1u;
-            const size_t valid_bytes = (n * C + 7) / 8;
-            const char *qb = static_cast<const char *>(P.q);
-#pragma unroll 1
-            for (int r = 0; r < kRounds; ++r) {
-                const size_t e0 = wave_base + static_cast<size_t>(r) * kRound + static_cast<size_t>(lane) * kFpl;
-                const size_t off = e0 / 8 * C;  // e0 is a multiple of 16
-                u32x4 acc = {0, 0, 0, 0};
-                const bool full = off + 16 <= valid_bytes;
-                if (full) {
-                    int w = 0;
-                    for (; w + 4 <= W; w += 4) {
-                        u32x4 x[4];
+        }
+    } else {
+        // field rows: a lane owns 16 consecutive fields = 2 C bytes of every row
+        constexpr int C = IN;
+        constexpr int NWD = C / 2;  // 32-bit words per lane
+        constexpr uint32_t fmask = (1u << C) - 1u;
+        const size_t valid_bytes = (n * C + 7) / 8;
+        const size_t e0 = wave_base + static_cast<size_t>(lane) * 16;
+        const size_t off = e0 / 8 * C;
+        const char *qb = static_cast<const char *>(P.q) + off;
+        uint32_t acc[NWD];
 #pragma unroll
-                        for (int k = 0; k < 4; ++k)
-                            x[k] = *reinterpret_cast<const u32x4 *>(qb + static_cast<size_t>(w + k) * P.q_stride_bytes + off);
+        for (int i = 0; i < NWD; ++i) acc[i] = 0;
+        if (off + 2 * C <= valid_bytes) {
+            int w = 0;
+            for (; w + 4 <= W; w += 4) {
+                uint32_t x[4][NWD];
 #pragma unroll
-                        for (int k = 0; k < 4; ++k) acc += x[k];
-                    }
-                    for (; w < W; ++w) acc += *reinterpret_cast<const u32x4 *>(qb + static_cast<size_t>(w) * P.q_stride_bytes + off);
-                    if (P.sum_out) *reinterpret_cast<u32x4 *>(static_cast<char *>(P.sum_out) + off) = acc;
-                } else if (off < valid_bytes) {
-                    // the lane that holds the end of the row: byte by byte, pad fields dropped
-                    const int nb = static_cast<int>(valid_bytes - off);
-                    for (int w = 0; w < W; ++w) {
-                        const uint8_t *src = reinterpret_cast<const uint8_t *>(qb + static_cast<size_t>(w) * P.q_stride_bytes + off);
+                for (int k = 0; k < 4; ++k) load_words<NWD>(qb + static_cast<size_t>(w + k) * P.q_stride_bytes, x[k]);
 #pragma unroll
-                        for (int b = 0; b < 16; ++b)
-                            if (b < nb) acc[b >> 2] += static_cast<uint32_t>(src[b]) << (8 * (b & 3));
-                    }
+                for (int k = 0; k < 4; ++k)
 #pragma unroll
-                    for (int f = 0; f < kFpl; ++f)
-                        if (e0 + f >= n) acc[(f * C) >> 5] &= ~(fmask << ((f * C) & 31));
-                    if (P.sum_out) {
-                        uint8_t *dst = reinterpret_cast<uint8_t *>(static_cast<char *>(P.sum_out) + off);
+                    for (int i = 0; i < NWD; ++i) acc[i] += x[k][i];
+            }
+            for (; w < W; ++w) {
+                uint32_t x[NWD];
+                load_words<NWD>(qb + static_cast<size_t>(w) * P.q_stride_bytes, x);
 #pragma unroll
-                        for (int b = 0; b < 16; ++b)
-                            if (b < nb) dst[b] = static_cast<uint8_t>(acc[b >> 2] >> (8 * (b & 3)));
-                    }
-                }
-                uint64_t gt = 0, eq = 0;
+                for (int i = 0; i < NWD; ++i) acc[i] += x[i];
+            }
+            if (P.sum_out) store_words<NWD>(static_cast<char *>(P.sum_out) + off, acc);
+        } else if (off < valid_bytes) {
+            // the lane that holds the end of the row: byte by byte, pad fields dropped
+            const int nb = static_cast<int>(valid_bytes - off);
+            for (int w = 0; w < W; ++w) {
+                const uint8_t *src = reinterpret_cast<const uint8_t *>(qb + static_cast<size_t>(w) * P.q_stride_bytes);
 #pragma unroll
-                for (int f = 0; f < kFpl; ++f) {
-                    const uint32_t K = (acc[(f * C) >> 5] >> ((f * C) & 31)) & fmask;
-                    gt |= static_cast<uint64_t>(K > static_cast<uint32_t>(T)) << f;
-                    eq |= static_cast<uint64_t>(K == static_cast<uint32_t>(T)) << f;
-                }
-                uint64_t pos, nz;
-                vote_planes(gt, eq, W, P.tie, pos, nz);
-                const uint64_t vm = valid_mask(e0, n) & (kFpl == 64 ? ~0ull : ((1ull << (kFpl & 63)) - 1ull));
-                pos &= vm;
-                nz &= vm;
-                if (kFpl == 64) {
-                    s_pos[wave][lane] = pos;
-                    s_nz[wave][lane] = nz;
-                } else if (kFpl == 32) {
-                    reinterpret_cast<uint32_t *>(s_pos[wave])[r * kWave + lane] = static_cast<uint32_t>(pos);
-                    reinterpret_cast<uint32_t *>(s_nz[wave])[r * kWave + lane] = static_cast<uint32_t>(nz);
-                } else {
-                    reinterpret_cast<uint16_t *>(s_pos[wave])[r * kWave + lane] = static_cast<uint16_t>(pos);
-                    reinterpret_cast<uint16_t *>(s_nz[wave])[r * kWave + lane] = static_cast<uint16_t>(nz);
-                }
+                for (int b = 0; b < 2 * C; ++b)
+                    if (b < nb) acc[b >> 2] += static_cast<uint32_t>(src[b]) << (8 * (b & 3));
+            }
+#pragma unroll
+            for (int f = 0; f < 16; ++f)
+                if (e0 + f >= n) acc[(f * C) >> 5] &= ~(fmask << ((f * C) & 31));
+            if (P.sum_out) {
+                uint8_t *dst = reinterpret_cast<uint8_t *>(static_cast<char *>(P.sum_out) + off);
+#pragma unroll
+                for (int b = 0; b < 2 * C; ++b)
+                    if (b < nb) dst[b] = static_cast<uint8_t>(acc[b >> 2] >> (8 * (b & 3)));
             }
         }
+        uint64_t gt = 0, eq = 0;
+#pragma unroll
+        for (int f = 0; f < 16; ++f) {
+            const uint32_t K = (acc[(f * C) >> 5] >> ((f * C) & 31)) & fmask;
+            gt |= static_cast<uint64_t>(K > static_cast<uint32_t>(T)) << f;
+            eq |= static_cast<uint64_t>(K == static_cast<uint32_t>(T)) << f;
+        }
+        uint64_t pos, nz;
+        vote_planes(gt, eq, W, P.tie, pos, nz);
+        const uint64_t vm = valid_mask(e0, n) & 0xFFFFull;
+        reinterpret_cast<uint16_t *>(s_pos[wave])[lane] = static_cast<uint16_t>(pos & vm);
+        reinterpret_cast<uint16_t *>(s_nz[wave])[lane] = static_cast<uint16_t>(nz & vm);
     }
-    __syncthreads();
+    wave_lds_sync();
 
-    if (IN != IN_PLANES && IN != IN_BITS && active) {
+    if (IN != IN_PLANES && IN != IN_BITS && lane < kAggWords) {
         // planes for the caller, from LDS in word order
         const size_t jw = wave_base / 64 + lane;
         if (jw * 64 < n) {
@@ -240,47 +331,40 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggParams P)
     }
 
     // ---------------------------------------------------------------- phase C
-    if (!(APPLY || KOUT) || !active) return;
+    if (!(APPLY || KOUT)) return;
     const uint8_t *pos8 = reinterpret_cast<const uint8_t *>(s_pos[wave]);
     const uint8_t *nz8 = reinterpret_cast<const uint8_t *>(s_nz[wave]);
     const float lr = P.lr, wd = P.wd;
     const int sh = (lane & 1) * 4;
 
-    if (APPLY && wave_base + kAggWave <= n) {
-        constexpr int U = 4;
-#pragma unroll 1
-        for (int t0 = 0; t0 < kAggTiles; t0 += U) {
-            f32x4 th[U];
+    if (APPLY && full_wave) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) th[u] = load4(P.theta + wave_base + (t0 + u) * 256 + lane * 4);
+        for (int t = 0; t < kAggTiles; ++t) {
+            const int byte = t * 32 + (lane >> 1);
+            const uint32_t pn = pos8[byte] >> sh, zn = nz8[byte] >> sh;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int byte = (t0 + u) * 32 + (lane >> 1);
-                const uint32_t pn = pos8[byte] >> sh, zn = nz8[byte] >> sh;
+            for (int k = 0; k < 4; ++k) {
+                const float uf = ((zn >> k) & 1u) ? (((pn >> k) & 1u) ? 1.0f : -1.0f) : 0.0f;
+                th[t][k] = __builtin_fmaf(-lr, __builtin_fmaf(wd, th[t][k], uf), th[t][k]);
+            }
+        }
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const float uf = ((zn >> k) & 1u) ? (((pn >> k) & 1u) ? 1.0f : -1.0f) : 0.0f;
-                    th[u][k] = __builtin_fmaf(-lr, __builtin_fmaf(wd, th[u][k], uf), th[u][k]);
-                }
+        for (int t = 0; t < kAggTiles; ++t) store4(P.theta + wave_base + t * 256 + lane * 4, th[t]);
+        for (int w = 0; w < P.n_m; ++w) {
+            float *mrow = P.m + static_cast<size_t>(w) * P.m_stride;
+            const void *grow = static_cast<const char *>(P.g) + static_cast<size_t>(w) * P.g_stride * Grad<GDT>::kBytes;
+            f32x4 mv[kAggTiles], gv[kAggTiles];
+#pragma unroll
+            for (int t = 0; t < kAggTiles; ++t) {
+                const size_t e = wave_base + t * 256 + lane * 4;
+                mv[t] = load4(mrow + e);
+                gv[t] = Grad<GDT>::load4(grow, e);
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) store4(P.theta + wave_base + (t0 + u) * 256 + lane * 4, th[u]);
-            for (int w = 0; w < P.n_m; ++w) {
-                float *mrow = P.m + static_cast<size_t>(w) * P.m_stride;
-                const void *grow = static_cast<const char *>(P.g) + static_cast<size_t>(w) * P.g_stride * Grad<GDT>::kBytes;
-                f32x4 mv[U], gv[U];
+            for (int t = 0; t < kAggTiles; ++t) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const size_t e = wave_base + (t0 + u) * 256 + lane * 4;
-                    mv[u] = load4(mrow + e);
-                    gv[u] = Grad<GDT>::load4(grow, e);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) mv[u][k] = momentum_step(mv[u][k], gv[u][k], P.beta2, P.omb2);
-                    store4(mrow + wave_base + (t0 + u) * 256 + lane * 4, mv[u]);
-                }
+                for (int k = 0; k < 4; ++k) mv[t][k] = momentum_step(mv[t][k], gv[t][k], P.beta2, P.omb2);
+                store4(mrow + wave_base + t * 256 + lane * 4, mv[t]);
             }
         }
     } else if (APPLY) {
@@ -292,8 +376,8 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggParams P)
             const uint32_t pn = pos8[byte] >> sh, zn = nz8[byte] >> sh;
             for (int k = 0; k < 4 && e + k < n; ++k) {
                 const float uf = ((zn >> k) & 1u) ? (((pn >> k) & 1u) ? 1.0f : -1.0f) : 0.0f;
-                const float th = P.theta[e + k];
-                P.theta[e + k] = __builtin_fmaf(-lr, __builtin_fmaf(wd, th, uf), th);
+                const float v = P.theta[e + k];
+                P.theta[e + k] = __builtin_fmaf(-lr, __builtin_fmaf(wd, v, uf), v);
                 for (int w = 0; w < P.n_m; ++w) {
                     float *mrow = P.m + static_cast<size_t>(w) * P.m_stride;
                     const void *grow = static_cast<const char *>(P.g) + static_cast<size_t>(w) * P.g_stride * Grad<GDT>::kBytes;
@@ -337,7 +421,7 @@ template <int IN, int GDT, bool APPLY, bool KOUT>
 static hipError_t launch_one(const AggParams &P, hipStream_t s)
 {
     const unsigned grid = static_cast<unsigned>((P.n + kAggBlock - 1) / kAggBlock);
-    aggregate_kernel<IN, GDT, APPLY, KOUT><<<grid, kBlock, 0, s>>>(P);
+    aggregate_kernel<IN, GDT, APPLY, KOUT><<<grid, kAggThreads, 0, s>>>(P);
     return hipGetLastError();
 }
 

@@ -8,9 +8,13 @@
 
 namespace lc {
 
-constexpr int kAvgBlock = kBlock * 4;  // elements per workgroup
+#ifndef LC_AVG_THREADS
+#define LC_AVG_THREADS 256
+#endif
+constexpr int kAvgThreads = LC_AVG_THREADS;  // workgroup size
+constexpr int kAvgBlock = kAvgThreads * 4;   // elements per workgroup
 
-__global__ __launch_bounds__(kBlock) void momentum_avg_kernel(float *__restrict__ m, size_t stride, int W, size_t n, float inv_w)
+__global__ __launch_bounds__(kAvgThreads) void momentum_avg_kernel(float *__restrict__ m, size_t stride, int W, size_t n, float inv_w)
 {
     const size_t e = static_cast<size_t>(blockIdx.x) * kAvgBlock + threadIdx.x * 4;
     if (e >= n) return;
@@ -40,7 +44,7 @@ __global__ __launch_bounds__(kBlock) void momentum_avg_kernel(float *__restrict_
 hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStream_t s)
 {
     const unsigned grid = static_cast<unsigned>((n + kAvgBlock - 1) / kAvgBlock);
-    momentum_avg_kernel<<<grid, kBlock, 0, s>>>(m, stride, W, n, 1.0f / static_cast<float>(W));
+    momentum_avg_kernel<<<grid, kAvgThreads, 0, s>>>(m, stride, W, n, 1.0f / static_cast<float>(W));
     return hipGetLastError();
 }
 

@@ -17,9 +17,17 @@
 
 namespace lc {
 
-constexpr int kPackTiles = 4;
-constexpr int kPackWave = kPackTiles * 256;
-constexpr int kPackBlock = kPackWave * kWaves;
+#ifndef LC_PACK_TILES
+#define LC_PACK_TILES 1
+#endif
+#ifndef LC_PACK_THREADS
+#define LC_PACK_THREADS 64
+#endif
+constexpr int kPackTiles = LC_PACK_TILES;             // 256-element tiles per wave
+constexpr int kPackThreads = LC_PACK_THREADS;         // workgroup size
+constexpr int kPackWave = kPackTiles * 256;           // elements per wave
+constexpr int kPackBlock = kPackWave * (kPackThreads / kWave);
+static_assert(kPackTiles >= 1 && kPackTiles <= 8, "a lane of each 8-lane group stores one tile's dword");
 
 // bit that a value of the interpolation c maps to: 1 if c > 0, 0 if c < 0, and the
 // zero rule's bit when c is zero (either sign) or NaN.
@@ -50,7 +58,7 @@ __device__ __forceinline__ uint32_t or_reduce8(uint32_t v)
 }
 
 template <int GDT, int OUT_BITS, bool UPDATE_M>
-__global__ __launch_bounds__(kBlock) void local_update_pack_kernel(
+__global__ __launch_bounds__(kPackThreads) void local_update_pack_kernel(
     const void *__restrict__ g, size_t g_stride, float *__restrict__ m, size_t m_stride, size_t n,
     float beta1, float omb1, float beta2, float omb2, void *__restrict__ q, size_t q_stride_bytes,
     int zero_bit)
@@ -122,10 +130,10 @@ __global__ __launch_bounds__(kBlock) void local_update_pack_kernel(
         const bool valid = i < n;
         uint32_t bit = 0;
         if (valid) {
-            const float mm = mrow[i];
+            const float mm = ld_stream(mrow + i);
             const float gg = Grad<GDT>::load1(grow, i);
             bit = sign_to_bit(interpolate(mm, gg, beta1, omb1), z1);
-            if (UPDATE_M) mrow[i] = momentum_step(mm, gg, beta2, omb2);
+            if (UPDATE_M) st_stream(mrow + i, momentum_step(mm, gg, beta2, omb2));
         }
         const uint64_t mask = __ballot(bit != 0);
         if (!qrow) continue;
@@ -149,10 +157,10 @@ static hipError_t launch_pack(bool update_m, dim3 grid, hipStream_t s, const voi
                               size_t q_stride_bytes, int zero_bit)
 {
     if (update_m)
-        local_update_pack_kernel<GDT, OUT_BITS, true><<<grid, kBlock, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, beta2,
+        local_update_pack_kernel<GDT, OUT_BITS, true><<<grid, kPackThreads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, beta2,
                                                                               omb2, q, q_stride_bytes, zero_bit);
     else
-        local_update_pack_kernel<GDT, OUT_BITS, false><<<grid, kBlock, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, beta2,
+        local_update_pack_kernel<GDT, OUT_BITS, false><<<grid, kPackThreads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, beta2,
                                                                                omb2, q, q_stride_bytes, zero_bit);
     return hipGetLastError();
 }
