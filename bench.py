@@ -28,7 +28,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c1")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 25, help="parameters in the oracle's sample (0: skip)")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="parameters in the oracle's sample (0: skip)")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = host cores available, capped at 16")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="also run one plain device copy of BYTES (read BYTES, write BYTES) before the steps: "

@@ -108,8 +108,9 @@ int lc_apply_update(float *theta, const uint64_t *vote_pos, const uint64_t *vote
                     float beta2, void *stream);
 
 /* Section 5, momentum synchronisation: every row becomes the mean of the W rows (what
- * an averaging allreduce leaves on every worker).  fp32 sum in row order, then one
- * multiplication by 1/W. */
+ * an averaging allreduce leaves on every worker).  The W values of an element are summed
+ * in fp32 (partial sums over interleaved subsets of the rows, then their sum), and the
+ * total is multiplied once by 1/W; every row receives the same bits. */
 int lc_momentum_avg(float *m, size_t m_stride_elems, int W, size_t n, void *stream);
 
 /* Fused forms: lc_vote_1bit followed by lc_apply_update without writing the planes. */
