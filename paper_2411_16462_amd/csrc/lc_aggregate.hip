@@ -30,11 +30,14 @@
 namespace lc {
 
 #ifndef LC_AGG_THREADS
-#define LC_AGG_THREADS 64
+#define LC_AGG_THREADS 128
 #endif
 constexpr int kAggThreads = LC_AGG_THREADS;   // workgroup size; waves are independent
 constexpr int kWaves = kAggThreads / kWave;
-constexpr int kAggWords = 16;                 // packed words per wave
+#ifndef LC_AGG_WORDS
+#define LC_AGG_WORDS 16
+#endif
+constexpr int kAggWords = LC_AGG_WORDS;       // packed words per wave
 constexpr int kAggWave = kAggWords * 64;      // elements per wave
 constexpr int kAggBlock = kAggWave * kWaves;  // elements per workgroup
 constexpr int kAggTiles = kAggWave / 256;
@@ -146,11 +149,14 @@ __device__ __forceinline__ void load_words(const char *p, uint32_t (&x)[NWD])
         x[0] = v.x;
         x[1] = v.y;
     } else {
-        const u32x4 v = ld_packed(reinterpret_cast<const u32x4 *>(p));
-        x[0] = v.x;
-        x[1] = v.y;
-        x[2] = v.z;
-        x[3] = v.w;
+#pragma unroll
+        for (int h = 0; h < NWD / 4; ++h) {
+            const u32x4 v = ld_packed(reinterpret_cast<const u32x4 *>(p) + h);
+            x[4 * h + 0] = v.x;
+            x[4 * h + 1] = v.y;
+            x[4 * h + 2] = v.z;
+            x[4 * h + 3] = v.w;
+        }
     }
 }
 
@@ -163,12 +169,15 @@ __device__ __forceinline__ void store_words(char *p, const uint32_t (&x)[NWD])
         u32x2 v = {x[0], x[1]};
         st_stream(reinterpret_cast<u32x2 *>(p), v);
     } else {
-        u32x4 v = {x[0], x[1], x[2], x[3]};
-        st_stream(reinterpret_cast<u32x4 *>(p), v);
+#pragma unroll
+        for (int h = 0; h < NWD / 4; ++h) {
+            u32x4 v = {x[4 * h + 0], x[4 * h + 1], x[4 * h + 2], x[4 * h + 3]};
+            st_stream(reinterpret_cast<u32x4 *>(p) + h, v);
+        }
     }
 }
 
-template <int IN, int GDT, bool APPLY, bool KOUT>
+template <int IN, int GDT, bool APPLY, bool MOM, bool KOUT>
 __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams P)
 {
     __shared__ uint64_t s_pos[kWaves][kAggWords];
@@ -189,6 +198,17 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
     if (APPLY && full_wave) {
 #pragma unroll
         for (int t = 0; t < kAggTiles; ++t) th[t] = load4(P.theta + wave_base + t * 256 + lane * 4);
+    }
+
+    // ... and so do the loads of the first momentum / gradient stream
+    f32x4 mv0[MOM ? kAggTiles : 1], gv0[MOM ? kAggTiles : 1];
+    if (MOM && full_wave) {
+#pragma unroll
+        for (int t = 0; t < kAggTiles; ++t) {
+            const size_t e = wave_base + t * 256 + lane * 4;
+            mv0[MOM ? t : 0] = load4(P.m + e);
+            gv0[MOM ? t : 0] = Grad<GDT>::load4(P.g, e);
+        }
     }
 
     // ---------------------------------------------------------------- phase A + B
@@ -237,8 +257,8 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
             const bool have = vm && (ph + k * kPhases < W);
             ripple(c, have ? ld_packed(qp + static_cast<size_t>(k) * step4) : 0ull, 0);
         }
-        add_partner(c, lane, 16, np);
-        add_partner(c, lane, 32, np);
+#pragma unroll
+        for (int mask = kAggWords; mask < kWave; mask <<= 1) add_partner(c, lane, mask, np);
         uint64_t gt, eq, pos, nz;
         compare_planes(c, T, gt, eq);
         vote_planes(gt, eq, W, P.tie, pos, nz);
@@ -258,18 +278,21 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
             }
         }
     } else {
-        // field rows: a lane owns 16 consecutive fields = 2 C bytes of every row
+        // field rows: a lane owns kFpl consecutive fields of every row
         constexpr int C = IN;
-        constexpr int NWD = C / 2;  // 32-bit words per lane
+        constexpr int kFpl = kAggWave / kWave;   // fields per lane
+        constexpr int kLaneBytes = kFpl * C / 8;
+        constexpr int NWD = kLaneBytes / 4;      // 32-bit words per lane
+        static_assert(kLaneBytes >= 4, "a lane needs at least one 32-bit word of fields");
         constexpr uint32_t fmask = (1u << C) - 1u;
         const size_t valid_bytes = (n * C + 7) / 8;
-        const size_t e0 = wave_base + static_cast<size_t>(lane) * 16;
-        const size_t off = e0 / 8 * C;
+        const size_t e0 = wave_base + static_cast<size_t>(lane) * kFpl;
+        const size_t off = e0 / 8 * C;  // e0 is a multiple of 16
         const char *qb = static_cast<const char *>(P.q) + off;
         uint32_t acc[NWD];
 #pragma unroll
         for (int i = 0; i < NWD; ++i) acc[i] = 0;
-        if (off + 2 * C <= valid_bytes) {
+        if (off + kLaneBytes <= valid_bytes) {
             int w = 0;
             for (; w + 4 <= W; w += 4) {
                 uint32_t x[4][NWD];
@@ -293,31 +316,37 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
             for (int w = 0; w < W; ++w) {
                 const uint8_t *src = reinterpret_cast<const uint8_t *>(qb + static_cast<size_t>(w) * P.q_stride_bytes);
 #pragma unroll
-                for (int b = 0; b < 2 * C; ++b)
+                for (int b = 0; b < kLaneBytes; ++b)
                     if (b < nb) acc[b >> 2] += static_cast<uint32_t>(src[b]) << (8 * (b & 3));
             }
 #pragma unroll
-            for (int f = 0; f < 16; ++f)
+            for (int f = 0; f < kFpl; ++f)
                 if (e0 + f >= n) acc[(f * C) >> 5] &= ~(fmask << ((f * C) & 31));
             if (P.sum_out) {
                 uint8_t *dst = reinterpret_cast<uint8_t *>(static_cast<char *>(P.sum_out) + off);
 #pragma unroll
-                for (int b = 0; b < 2 * C; ++b)
+                for (int b = 0; b < kLaneBytes; ++b)
                     if (b < nb) dst[b] = static_cast<uint8_t>(acc[b >> 2] >> (8 * (b & 3)));
             }
         }
         uint64_t gt = 0, eq = 0;
 #pragma unroll
-        for (int f = 0; f < 16; ++f) {
+        for (int f = 0; f < kFpl; ++f) {
             const uint32_t K = (acc[(f * C) >> 5] >> ((f * C) & 31)) & fmask;
             gt |= static_cast<uint64_t>(K > static_cast<uint32_t>(T)) << f;
             eq |= static_cast<uint64_t>(K == static_cast<uint32_t>(T)) << f;
         }
         uint64_t pos, nz;
         vote_planes(gt, eq, W, P.tie, pos, nz);
-        const uint64_t vm = valid_mask(e0, n) & 0xFFFFull;
-        reinterpret_cast<uint16_t *>(s_pos[wave])[lane] = static_cast<uint16_t>(pos & vm);
-        reinterpret_cast<uint16_t *>(s_nz[wave])[lane] = static_cast<uint16_t>(nz & vm);
+        const uint64_t vm = valid_mask(e0, n) & ((1ull << kFpl) - 1ull);
+        if constexpr (kFpl == 16) {
+            reinterpret_cast<uint16_t *>(s_pos[wave])[lane] = static_cast<uint16_t>(pos & vm);
+            reinterpret_cast<uint16_t *>(s_nz[wave])[lane] = static_cast<uint16_t>(nz & vm);
+        } else {
+            static_assert(kFpl == 32, "16 or 32 fields per lane");
+            reinterpret_cast<uint32_t *>(s_pos[wave])[lane] = static_cast<uint32_t>(pos & vm);
+            reinterpret_cast<uint32_t *>(s_nz[wave])[lane] = static_cast<uint32_t>(nz & vm);
+        }
     }
     wave_lds_sync();
 
@@ -350,7 +379,17 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
         }
 #pragma unroll
         for (int t = 0; t < kAggTiles; ++t) store4(P.theta + wave_base + t * 256 + lane * 4, th[t]);
-        for (int w = 0; w < P.n_m; ++w) {
+        if (MOM) {
+#pragma unroll
+            for (int t = 0; t < kAggTiles; ++t) {
+                f32x4 &mv = mv0[MOM ? t : 0];
+                const f32x4 gv = gv0[MOM ? t : 0];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) mv[k] = momentum_step(mv[k], gv[k], P.beta2, P.omb2);
+                store4(P.m + wave_base + t * 256 + lane * 4, mv);
+            }
+        }
+        for (int w = 1; MOM && w < P.n_m; ++w) {
             float *mrow = P.m + static_cast<size_t>(w) * P.m_stride;
             const void *grow = static_cast<const char *>(P.g) + static_cast<size_t>(w) * P.g_stride * Grad<GDT>::kBytes;
             f32x4 mv[kAggTiles], gv[kAggTiles];
@@ -378,7 +417,7 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
                 const float uf = ((zn >> k) & 1u) ? (((pn >> k) & 1u) ? 1.0f : -1.0f) : 0.0f;
                 const float v = P.theta[e + k];
                 P.theta[e + k] = __builtin_fmaf(-lr, __builtin_fmaf(wd, v, uf), v);
-                for (int w = 0; w < P.n_m; ++w) {
+                for (int w = 0; MOM && w < P.n_m; ++w) {
                     float *mrow = P.m + static_cast<size_t>(w) * P.m_stride;
                     const void *grow = static_cast<const char *>(P.g) + static_cast<size_t>(w) * P.g_stride * Grad<GDT>::kBytes;
                     mrow[e + k] = momentum_step(mrow[e + k], Grad<GDT>::load1(grow, e + k), P.beta2, P.omb2);
@@ -417,20 +456,21 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
     }
 }
 
-template <int IN, int GDT, bool APPLY, bool KOUT>
+template <int IN, int GDT, bool APPLY, bool MOM, bool KOUT>
 static hipError_t launch_one(const AggParams &P, hipStream_t s)
 {
     const unsigned grid = static_cast<unsigned>((P.n + kAggBlock - 1) / kAggBlock);
-    aggregate_kernel<IN, GDT, APPLY, KOUT><<<grid, kAggThreads, 0, s>>>(P);
+    aggregate_kernel<IN, GDT, APPLY, MOM, KOUT><<<grid, kAggThreads, 0, s>>>(P);
     return hipGetLastError();
 }
 
 template <int IN, bool KOUT>
 static hipError_t launch_in(const AggParams &P, bool apply, int g_dtype, hipStream_t s)
 {
-    if (!apply) return launch_one<IN, LC_F32, false, KOUT>(P, s);
-    if (g_dtype == LC_BF16) return launch_one<IN, LC_BF16, true, KOUT>(P, s);
-    return launch_one<IN, LC_F32, true, KOUT>(P, s);
+    if (!apply) return launch_one<IN, LC_F32, false, false, KOUT>(P, s);
+    if (P.n_m == 0) return launch_one<IN, LC_F32, true, false, KOUT>(P, s);
+    if (g_dtype == LC_BF16) return launch_one<IN, LC_BF16, true, true, KOUT>(P, s);
+    return launch_one<IN, LC_F32, true, true, KOUT>(P, s);
 }
 
 // Host launcher; arguments were validated by the caller.  in_kind: 0 planes, 1 bits,
