@@ -30,6 +30,9 @@ def parse():
     ap.add_argument("--workload", default="c1")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="parameters in the oracle's sample (0: skip)")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = host cores available, capped at 16")
+    ap.add_argument("--per-tensor", action="store_true",
+                    help="1-bit workloads with a tensor list: one pair of calls per tensor instead of one per arena "
+                         "(shows the small-tensor launch overhead; not the headline configuration)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="also run one plain device copy of BYTES (read BYTES, write BYTES) before the steps: "
                          "the reference point for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -58,7 +61,7 @@ class Kernel:
         return sum(a.elapsed_time(b) for a, b in self.events) / max(1, len(self.events))
 
 
-def build_step(wl, torch, lc, synth):
+def build_step(wl, torch, lc, synth, per_tensor=False):
     """Allocate the workload on cuda:0 and return (kernels, state) for one step."""
     dev = "cuda"
     n, W = wl.n, wl.W
@@ -83,7 +86,27 @@ def build_step(wl, torch, lc, synth):
     gd = lc.LC_BF16 if wl.g_dtype == "bf16" else lc.LC_F32
     gb = 2 if wl.g_dtype == "bf16" else 4
     st.update(theta=theta, m=m, g=g)
-    if wl.mode == "1bit":
+    if wl.mode == "1bit" and per_tensor and wl.tensors:
+        q = torch.zeros((W, synth.round_up(nw, 8)), dtype=torch.int64, device=dev)
+        st["q"] = q
+        spans, off = [], 0
+        for _, sz in wl.tensors:
+            assert sz % 64 == 0
+            spans.append((off, sz))
+            off += sz
+
+        def pack_all():
+            for o, sz in spans:
+                lc.lc_local_update_pack(g[:, o:], g.stride(0), gd, m[:, o:], m.stride(0), W, sz, hp["beta1"], 1,
+                                        hp["beta2"], 1, q[:, o // 64:], q.stride(0) * 8, step_no[0], lc.LC_ZERO_ALT)
+
+        def vote_all():
+            for o, sz in spans:
+                lc.lc_vote_apply_1bit(q[:, o // 64:], q.stride(0), W, sz, step_no[0], lc.LC_TIE_ZERO, theta[o:],
+                                      hp["lr"], hp["wd"], None, 0, None, 0, lc.LC_F32, 0, hp["beta2"])
+        kernels.append(Kernel("local_update_pack[per tensor]", pack_all, W * n * (4 + gb + 4 + 1 / 8)))
+        kernels.append(Kernel("vote_apply_1bit[per tensor]", vote_all, n * (W / 8 + 8)))
+    elif wl.mode == "1bit":
         q = torch.zeros((W, synth.round_up(nw, 8)), dtype=torch.int64, device=dev)
         st["q"] = q
         kernels.append(Kernel(
@@ -194,7 +217,7 @@ def main():
     lc.load()
     torch.cuda.set_device(0)
     wl = synth.workload(args.workload)
-    kernels, st, step_no = build_step(wl, torch, lc, synth)
+    kernels, st, step_no = build_step(wl, torch, lc, synth, args.per_tensor)
     torch.cuda.synchronize()
     if args.copy_calibration:
         src = torch.empty(args.copy_calibration, dtype=torch.uint8, device="cuda").fill_(1)
@@ -235,7 +258,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "n_params": wl.n, "workers": wl.W, "mode": wl.mode, "p": wl.p,
-                   "g_dtype": wl.g_dtype, "momentum_avg": wl.momentum_avg},
+                   "g_dtype": wl.g_dtype, "momentum_avg": wl.momentum_avg,
+                   "calls": "per tensor" if args.per_tensor else "one flat arena"},
         "step_alg_bytes": step_bytes, "step_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": roofline, "kernels": per_kernel,

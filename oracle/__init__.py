@@ -262,3 +262,73 @@ def step_pbit(theta, m, g, *, p, beta1, beta2, lr, wd, step, zero=ZERO_ALT, tie=
     m_new = np.stack([momentum(m[w], g[w], beta2, g_dtype) for w in range(W)])
     return dict(s=s, b=b, fields=fields, sum_fields=total, K=K, S=S, u=u, pos=pos, nz=nz,
                 theta=theta_new, m=m_new)
+
+
+# ---- L1 quantisation (Section 4.2, Equation 1 with p = 1) -------------------------------
+_local_c = _sig("orc_local_c", None, _vp, _vp, _i, _sz, _f, _vp)
+_abs_totals = _sig("orc_abs_totals", None, _vp, _sz, _vp)
+_l1_levels = _sig("orc_l1_levels", None, _vp, _sz, C.c_double, _i, _vp)
+_level_sum_sign = _sig("orc_level_sum_sign", _i, _vp, _i, _sz, _i, _u64, _i, _vp, _vp, _vp)
+
+
+def local_c(m, g, beta1, g_dtype=F32):
+    """Algorithm 1 line 3: the interpolation itself, float32."""
+    m = _arr(m, np.float32)
+    g = _grad(g, g_dtype)
+    c = np.empty(m.shape, np.float32)
+    _local_c(_p(m), _p(g), g_dtype, m.size, beta1, _p(c))
+    return c
+
+
+def mean_abs(x):
+    """M_1(x) = (1/d) sum |x_j| of Equation 1: the sum is formed without rounding (integer
+    totals per binary exponent, added as Python integers), rounded once to fp64, and
+    divided by d in fp64."""
+    x = _arr(x, np.float32).ravel()
+    totals = np.zeros(256, np.uint64)
+    _abs_totals(_p(x), x.size, _p(totals))
+    if totals[255]:
+        return float("nan")
+    exact = sum(int(t) << (e - 1) for e, t in enumerate(totals.tolist()) if t)   # units of 2^-149
+    return float(np.ldexp(float(exact), -149)) / x.size if x.size else 0.0
+
+
+def l1_levels(x, mean, L):
+    x = _arr(x, np.float32)
+    out = np.empty(x.shape, np.int8)
+    _l1_levels(_p(x), x.size, float(mean), L, _p(out))
+    return out
+
+
+def level_sum_sign(rows, L, step, tie_rule=TIE_ZERO):
+    """rows: (W, n) uint8 biased levels.  Returns K, S (int32), u (int8)."""
+    rows = _arr(rows, np.uint8)
+    W, n = rows.shape
+    K = np.empty(n, np.int32)
+    S = np.empty(n, np.int32)
+    u = np.empty(n, np.int8)
+    rc = _level_sum_sign(_p(rows), W, n, L, step, tie_rule, _p(K), _p(S), _p(u))
+    if rc:
+        raise OracleError(rc, "level_sum_sign")
+    return K, S, u
+
+
+def step_l1(theta, m, g, *, L, beta1, beta2, lr, wd, step, tie=TIE_ZERO, g_dtype=F32):
+    """One whole step with L1-quantised updates (Equation 1, Appendix F.1): every worker
+    scales its interpolation by L / (2 mean|c|), rounds, clamps to [-L, L] and sends
+    level + L as a byte; the bytes are summed, the sign of the summed levels moves theta."""
+    m = _arr(m, np.float32)
+    W, n = m.shape
+    if 2 * L * W > 255:
+        raise OracleError(ERR_RANGE, "step_l1")
+    c = np.stack([local_c(m[w], g[w], beta1, g_dtype) for w in range(W)])
+    means = np.array([mean_abs(c[w]) for w in range(W)])
+    levels = np.stack([l1_levels(c[w], means[w], L) for w in range(W)])
+    fields = (levels.astype(np.int16) + L).astype(np.uint8)
+    K, S, u = level_sum_sign(fields, L, step, tie)
+    assert np.array_equal(sum_bytes(fields), K.astype(np.uint8))
+    pos, nz = planes(u)
+    theta_new = apply(theta, u, lr, wd)
+    m_new = np.stack([momentum(m[w], g[w], beta2, g_dtype) for w in range(W)])
+    return dict(c=c, mean_abs=means, levels=levels, fields=fields, K=K, S=S, u=u, pos=pos, nz=nz,
+                theta=theta_new, m=m_new)

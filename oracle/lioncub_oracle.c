@@ -266,3 +266,73 @@ void orc_sum_bytes(const uint8_t *bytes, int W, size_t nbytes, uint8_t *out)
         out[j] = (uint8_t)(acc & 0xFFu);
     }
 }
+
+/* ==== L1 quantisation (Section 4.2, Equation 1 with p = 1) ======================== */
+
+/* The interpolation c of Algorithm 1 line 3 itself (same fp32 evaluation as above). */
+void orc_local_c(const float *m, const void *g, int g_dtype, size_t n, float beta1, float *c)
+{
+    const float omb1 = 1.0f - beta1;
+    for (size_t i = 0; i < n; ++i) {
+        const float t = omb1 * grad_at(g, g_dtype, i);
+        c[i] = fmaf(beta1, m[i], t);
+    }
+}
+
+/* Sum of |x_i| without any rounding.  A finite binary32 is an integer M < 2^24 times
+ * 2^(E-150) (E the biased exponent, denormals: E = 1 and no hidden bit), so the total of
+ * the integers M per exponent is exact in 64 bits for any n < 2^40.  totals[E] receives
+ * that integer; the caller forms sum_E totals[E] * 2^(E-150) with big integers.  Values
+ * that are not finite are counted in totals[255] and make the mean undefined. */
+void orc_abs_totals(const float *x, size_t n, uint64_t totals[256])
+{
+    for (int e = 0; e < 256; ++e) totals[e] = 0;
+    for (size_t i = 0; i < n; ++i) {
+        uint32_t bits;
+        memcpy(&bits, &x[i], sizeof bits);
+        const uint32_t e = (bits >> 23) & 0xFFu;
+        const uint32_t frac = bits & 0x7FFFFFu;
+        if (e == 255) totals[255] += 1;
+        else if (e == 0) totals[1] += frac;
+        else totals[e] += frac | 0x800000u;
+    }
+}
+
+/* Equation 1 with p = 1:  Q_1(x)_i = clamp(round(L / (2 M_1) * x_i), L),  L = 2^(n-1) - 1,
+ * M_1 = mean |x_j| (passed in, fp64).  The scale L / (2 M_1) is rounded once to fp32, the
+ * product with x_i is one fp32 multiplication, and round() is round-half-to-even (the
+ * paper does not say; it is what its PyTorch implementation's round does).  M_1 = 0 (all
+ * entries zero) gives all levels 0. */
+void orc_l1_levels(const float *x, size_t n, double mean_abs, int L, int8_t *level)
+{
+    const float scale = (mean_abs > 0.0) ? (float)((double)L / (2.0 * mean_abs)) : 0.0f;
+    for (size_t i = 0; i < n; ++i) {
+        float r = rintf(scale * x[i]);
+        if (r > (float)L) r = (float)L;
+        if (r < (float)-L) r = (float)-L;
+        level[i] = (mean_abs > 0.0) ? (int8_t)r : 0;
+    }
+}
+
+/* Appendix F.1: levels in [-L, L] travel as unsigned bytes level + L in [0, 2L], so that
+ * a plain integer sum over W workers stays below 256 when 2 L W <= 255 (L = 15, 8 workers:
+ * 240).  K = sum of the bytes, S = K - W L = sum of the levels, u = sign(S) (Algorithm 1
+ * lines 4-5), ties as in orc_count_sign.  rows: W rows of n bytes. */
+int orc_level_sum_sign(const uint8_t *rows, int W, size_t n, int L, uint64_t step, int tie_rule,
+                       int32_t *K, int32_t *S, int8_t *u)
+{
+    if (W < 1 || L < 1 || L > 127) return ORC_ERR_ARG;
+    if (2 * L * W > 255) return ORC_ERR_RANGE;
+    const int alt = (step % 2u == 1u) ? 1 : -1;
+    for (size_t i = 0; i < n; ++i) {
+        int32_t k = 0;
+        for (int w = 0; w < W; ++w) k += rows[(size_t)w * n + i];
+        const int32_t sum = k - W * L;
+        int v = (sum > 0) - (sum < 0);
+        if (v == 0 && tie_rule == ORC_TIE_ALT) v = alt;
+        if (K) K[i] = k;
+        if (S) S[i] = sum;
+        if (u) u[i] = (int8_t)v;
+    }
+    return ORC_OK;
+}

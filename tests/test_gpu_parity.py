@@ -258,3 +258,82 @@ def test_multi_step_trajectory():
         case.snapshot()
         out = run_1bit(case, step)
         check_1bit(out, oracle_step(case, HP, step))
+
+
+def test_side_stream_and_read_only_inputs():
+    """Calls on a non-default stream, given as the `stream` argument, while the default
+    stream is busy; g and q are read-only for the calls that take them as inputs."""
+    n, W = 300000 + 13, 8
+    case = Case(n, W, seed=11000, m_spread=1.0)
+    ref = oracle_step(case, HP, 3)
+    side = torch.cuda.Stream()
+    nw = nwords(n)
+    q = guarded(W, nw * 8, case.device)
+    g_before = case.g.clone()
+    busy = torch.randn(1 << 24, device="cuda")
+    side.wait_stream(torch.cuda.current_stream())
+    for _ in range(20):
+        busy = busy * 1.0001 + 1.0                           # keeps the default stream occupied
+    lc.lc_local_update_pack(case.g, case.g.stride(0), case.gd, case.m, case.m.stride(0), W, n, HP["beta1"], 1,
+                            HP["beta2"], 1, q, q.stride(0), 3, lc.LC_ZERO_ALT, stream=side)
+    q_before = None
+    with torch.cuda.stream(side):
+        q_before = q.clone()
+    lc.lc_vote_apply_1bit(q, q.stride(0) // 8, W, n, 3, lc.LC_TIE_ZERO, case.theta, HP["lr"], HP["wd"], None, 0, None, 0,
+                          lc.LC_F32, 0, HP["beta2"], stream=side.cuda_stream)
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert np.array_equal(words_of(q, nw), ref["words"])
+    assert_close(case.theta.cpu().numpy(), ref["theta"], "theta")
+    assert_close(case.m.cpu().numpy(), ref["m"], "momentum")
+    assert torch.equal(case.g, g_before) and torch.equal(q, q_before)
+
+
+def test_per_tensor_calls_equal_one_arena_call():
+    """A model as one flat arena, or one call per tensor at 64-aligned offsets (per-group
+    learning rates need that): the same bits either way."""
+    sizes = [64 * 37, 768, 768 * 5, 64, 2304, 64 * 129, 768 * 3 + 64 * 2, 4096 * 3, 1024 + 64]
+    n, W = sum(sizes), 4
+    a = Case(n, W, seed=12000, m_scale=0.0)
+    b = Case(n, W, seed=12000, m_scale=0.0)
+    nw = n // 64
+    qa, qb = guarded(W, nw * 8, a.device), guarded(W, nw * 8, b.device)
+    lc.lc_local_update_pack(a.g, a.g.stride(0), a.gd, a.m, a.m.stride(0), W, n, HP["beta1"], 1, HP["beta2"], 1, qa,
+                            qa.stride(0), 1, lc.LC_ZERO_ALT)
+    lc.lc_vote_apply_1bit(qa, qa.stride(0) // 8, W, n, 1, lc.LC_TIE_ZERO, a.theta, HP["lr"], HP["wd"], None, 0, None, 0,
+                          lc.LC_F32, 0, HP["beta2"])
+    off = 0
+    for sz in sizes:
+        lc.lc_local_update_pack(b.g[:, off:], b.g.stride(0), b.gd, b.m[:, off:], b.m.stride(0), W, sz, HP["beta1"], 1,
+                                HP["beta2"], 1, qb[:, off // 8:], qb.stride(0), 1, lc.LC_ZERO_ALT)
+        lc.lc_vote_apply_1bit(qb[:, off // 8:], qb.stride(0) // 8, W, sz, 1, lc.LC_TIE_ZERO, b.theta[off:], HP["lr"],
+                              HP["wd"], None, 0, None, 0, lc.LC_F32, 0, HP["beta2"])
+        off += sz
+    torch.cuda.synchronize()
+    assert torch.equal(qa, qb) and torch.equal(a.theta, b.theta) and torch.equal(a.m, b.m)
+    check = oracle_step(a, HP, 1)
+    assert np.array_equal(words_of(qa, nw), check["words"])
+    assert_close(a.theta.cpu().numpy(), check["theta"], "theta")
+
+
+def test_errors_leave_buffers_untouched():
+    """Argument errors are found on the host before any launch: nothing is written."""
+    n, W = 5000, 4
+    case = Case(n, W, seed=13000)
+    q = guarded(W, nwords(n) * 8, case.device)
+    calls = [
+        lambda: lc.lc_local_update_pack(case.g, case.g.stride(0), case.gd, case.m[:, 1:], case.m.stride(0), W, n - 1, 0.9,
+                                        1, 0.99, 1, q, q.stride(0), 1, lc.LC_ZERO_ALT, check=False),       # m misaligned
+        lambda: lc.lc_local_update_pack(case.g, case.g.stride(0), case.gd, case.m, case.m.stride(0), W, n, 0.9, 1, 0.99,
+                                        3, q, q.stride(0), 1, lc.LC_ZERO_ALT, check=False),                # bad width
+        lambda: lc.lc_pbit_sum_apply(q, q.stride(0), 1, 16, n, 4, None, 1, lc.LC_TIE_ZERO, case.theta, 1e-4, 0.1, None,
+                                     0, None, 0, lc.LC_F32, 0, 0.99, check=False),                         # 16 workers, p = 4
+        lambda: lc.lc_vote_apply_1bit(q, q.stride(0) // 8, W, n, 1, lc.LC_TIE_ZERO, case.theta[1:], 1e-4, 0.1, None, 0,
+                                      None, 0, lc.LC_F32, 0, 0.99, check=False),                           # theta misaligned
+        lambda: lc.lc_momentum_avg(case.m[:, 2:], case.m.stride(0), W, n - 2, check=False),                # 8-byte aligned only
+    ]
+    want = [lc.LC_ERR_ALIGN, lc.LC_ERR_MODE, lc.LC_ERR_RANGE, lc.LC_ERR_ALIGN, lc.LC_ERR_ALIGN]
+    assert [c() for c in calls] == want
+    torch.cuda.synchronize()
+    assert (q == SENTINEL).all().item()
+    assert np.array_equal(case.m.cpu().numpy(), case.m0) and np.array_equal(case.theta.cpu().numpy(), case.theta0)
