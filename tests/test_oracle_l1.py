@@ -105,7 +105,7 @@ def test_equation1_properties():
     assert (np.abs(lv[np.abs(x) >= 2 * M * (1 + 1e-6)]) == L).all()                  # clamp beyond 2 M_1
     assert (lv[np.abs(x) < M / L * (1 - 1e-6)] == 0).all()                           # |scale x| < 1/2 -> 0
     assert (np.sign(lv) * np.sign(x) >= 0).all()                                     # never flips a sign
-    c = np.full(64, -0.37, np.float32)                                               # constant vector: M_1 = |a|
+    c = np.full(64, -0.5, np.float32)                       # constant vector: M_1 = |a| = 0.5, scale = L exactly
     assert set(orc.l1_levels(c, orc.mean_abs(c), 15).tolist()) == {-8}               # round(7.5) -> 8 (half to even)
     assert set(orc.l1_levels(c, orc.mean_abs(c), 7).tolist()) == {-4}                # round(3.5) -> 4
     assert set(orc.l1_levels(c, orc.mean_abs(c), 3).tolist()) == {-2}                # round(1.5) -> 2
