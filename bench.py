@@ -8,7 +8,7 @@ ABI of liblioncub.so.  Prints ONE JSON line: params/s for the step, the roofline
 dominant kernel (algorithmic bytes / its mean launch duration from HIP events on the
 launch stream) and the CPU oracle timed on a bounded sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c0|c2|c3|c4]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c0|c2|c3|c4|l1]
 """
 import argparse
 import json
@@ -81,7 +81,8 @@ def build_step(wl, torch, lc, synth, per_tensor=False):
                                           m, m.stride(0), g, g.stride(0), lc.LC_F32, 1, hp["beta2"]),
             n * (W / 8 + 8 + 8 + 4)))
         return kernels, st, step_no
-    s = synth.make_state(n, W, seed=wl.seed, device=dev, g_dtype=wl.g_dtype, noise=wl.noise, m_spread=wl.m_spread)
+    s = synth.make_state(n, W, seed=wl.seed, device=dev, g_dtype=wl.g_dtype, noise=wl.noise, m_spread=wl.m_spread,
+                         dist=wl.dist)
     theta, m, g = s["theta"], s["m"], s["g"]
     gd = lc.LC_BF16 if wl.g_dtype == "bf16" else lc.LC_F32
     gb = 2 if wl.g_dtype == "bf16" else 4
@@ -119,6 +120,27 @@ def build_step(wl, torch, lc, synth, per_tensor=False):
             lambda: lc.lc_vote_apply_1bit(q, q.stride(0), W, n, step_no[0], lc.LC_TIE_ZERO, theta, hp["lr"], hp["wd"],
                                           None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
             n * (W / 8 + 8)))
+    elif wl.mode == "l1":
+        L = wl.levels
+        q = torch.zeros((W, synth.round_up(n, 64)), dtype=torch.uint8, device=dev)
+        sum_out = torch.zeros(synth.round_up(n, 64), dtype=torch.uint8, device=dev)
+        mean = torch.zeros(W, dtype=torch.float64, device=dev)
+        ws = torch.zeros(W * lc.LC_L1_WORKSPACE_WORDS, dtype=torch.int64, device=dev)
+        st.update(q=q, sum_out=sum_out, mean_abs=mean)
+        kernels.append(Kernel(
+            "l1_mean_abs",
+            lambda: lc.lc_l1_mean_abs(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], mean, ws),
+            W * n * (4 + gb)))
+        kernels.append(Kernel(
+            "l1_quantize_pack",
+            lambda: lc.lc_l1_quantize_pack(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], 1, hp["beta2"], L, mean,
+                                           q, q.stride(0)),
+            W * n * (4 + gb + 4 + 1)))
+        kernels.append(Kernel(
+            "level_sum_apply",
+            lambda: lc.lc_level_sum_apply(q, q.stride(0), W, n, L, sum_out, step_no[0], lc.LC_TIE_ZERO, theta, hp["lr"],
+                                          hp["wd"], None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
+            n * (W + 1 + 8)))
     else:
         C = lc.lc_container_bits(wl.p)
         fb = (n * C + 7) // 8
@@ -175,6 +197,8 @@ def cpu_baseline(wl, st, torch, sample, threads):
         def work(lo, hi):
             if wl.mode == "1bit":
                 r = orc.step_1bit(theta[lo:hi], m[:, lo:hi], g[:, lo:hi], g_dtype=gd, **kw)
+            elif wl.mode == "l1":   # per-chunk scales: same work per element as per-call scales
+                r = orc.step_l1(theta[lo:hi], m[:, lo:hi], g[:, lo:hi], L=wl.levels, g_dtype=gd, **kw)
             else:
                 r = orc.step_pbit(theta[lo:hi], m[:, lo:hi], g[:, lo:hi], p=wl.p, g_dtype=gd, **kw)
             if wl.momentum_avg:
@@ -258,7 +282,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "n_params": wl.n, "workers": wl.W, "mode": wl.mode, "p": wl.p,
-                   "g_dtype": wl.g_dtype, "momentum_avg": wl.momentum_avg,
+                   "g_dtype": wl.g_dtype, "momentum_avg": wl.momentum_avg, "levels": wl.levels,
                    "calls": "per tensor" if args.per_tensor else "one flat arena"},
         "step_alg_bytes": step_bytes, "step_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

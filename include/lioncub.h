@@ -128,6 +128,47 @@ int lc_pbit_sum_apply(const void *q, size_t q_stride_bytes, int in_bits, int W, 
                       size_t g_stride_elems, int g_dtype, int n_m, float beta2,
                       void *stream);
 
+/* ---- L1-quantised updates (Section 4.2, Equation 1 with p = 1; Appendix F.1) ---------
+ * Q_1(x)_i = clamp(round(L / (2 M_1(x)) * x_i), L) with M_1(x) = mean_j |x_j| and
+ * L = 2^(bits-1) - 1 levels on each side of zero (the paper's 8-bit allreduce among 8
+ * workers uses L = 15).  x is the worker's interpolation c of Algorithm 1 line 3, and
+ * M_1 is taken over the n elements of the call (one call per tensor gives per-tensor
+ * scales).  A level travels as the byte level + L in [0, 2L]; the W bytes of an element
+ * are added as integers, which needs 2 L W <= 255 (else LC_ERR_RANGE); the update is the
+ * sign of the summed levels, S = K - W L. */
+
+#define LC_L1_WORKSPACE_WORDS 12 /* uint64 words of device workspace per worker */
+
+/* First pass: mean_abs[w] = M_1(c_w), fp64.  The sum of |c| is formed without rounding
+ * (as a long integer, whatever the order of the additions), rounded once to fp64 and
+ * divided by n, so the result is reproducible bit for bit.  workspace: device buffer of
+ * W * LC_L1_WORKSPACE_WORDS uint64, overwritten.  mean_abs: W doubles on the device.
+ * n = 0 gives 0.  Inputs must be finite (a NaN or infinity makes mean_abs meaningless). */
+int lc_l1_mean_abs(const void *g, size_t g_stride_elems, int g_dtype, const float *m,
+                   size_t m_stride_elems, int W, size_t n, float beta1, double *mean_abs,
+                   uint64_t *workspace, void *stream);
+
+/* Second pass: the scale L / (2 mean_abs[w]) is rounded to fp32, multiplied with c in
+ * fp32, rounded to the nearest integer (ties to even), clamped to [-L, L] and stored as
+ * the byte level + L: q row w receives n bytes.  mean_abs[w] = 0 (all of c is zero) gives
+ * level 0 everywhere.  update_m as in lc_local_update_pack.  levels = L in 1..127. */
+int lc_l1_quantize_pack(const void *g, size_t g_stride_elems, int g_dtype, float *m,
+                        size_t m_stride_elems, int W, size_t n, float beta1, int update_m,
+                        float beta2, int levels, const double *mean_abs, uint8_t *q,
+                        size_t q_stride_bytes, void *stream);
+
+/* Sum of the W level bytes per element (sum_out, n bytes, may be NULL), and the sign of
+ * the summed levels as vote planes; a zero sum follows tie_rule. */
+int lc_level_sum_sign(const uint8_t *q, size_t q_stride_bytes, int W, size_t n, int levels,
+                      uint8_t *sum_out, uint64_t *vote_pos, uint64_t *vote_nz, uint64_t step,
+                      int tie_rule, void *stream);
+
+/* lc_level_sum_sign followed by lc_apply_update without writing the planes. */
+int lc_level_sum_apply(const uint8_t *q, size_t q_stride_bytes, int W, size_t n, int levels,
+                       uint8_t *sum_out, uint64_t step, int tie_rule, float *theta, float lr,
+                       float wd, float *m, size_t m_stride_elems, const void *g,
+                       size_t g_stride_elems, int g_dtype, int n_m, float beta2, void *stream);
+
 /* Smallest field width of 1, 2, 4, 8 bits that holds a p-bit value; -1 if p is not in
  * 1..8.  Host only. */
 int lc_container_bits(int p);

@@ -18,6 +18,7 @@ LC_F32, LC_BF16 = 0, 1
 LC_ZERO_ALT, LC_ZERO_POS, LC_ZERO_NEG = 0, 1, 2
 LC_TIE_ZERO, LC_TIE_ALT = 0, 1
 LC_MAX_W = 255
+LC_L1_WORKSPACE_WORDS = 12
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblioncub.so")
 
@@ -33,6 +34,10 @@ SIGNATURES = {
     "lc_vote_apply_1bit": (_i, [_vp, _sz, _i, _sz, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
     "lc_pbit_sum_apply": (_i, [_vp, _sz, _i, _i, _sz, _i, _vp, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i,
                                _f, _vp]),
+    "lc_l1_mean_abs": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _vp, _vp, _vp]),
+    "lc_l1_quantize_pack": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _i, _f, _i, _vp, _vp, _sz, _vp]),
+    "lc_level_sum_sign": (_i, [_vp, _sz, _i, _sz, _i, _vp, _vp, _vp, _u64, _i, _vp]),
+    "lc_level_sum_apply": (_i, [_vp, _sz, _i, _sz, _i, _vp, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
     "lc_container_bits": (_i, [_i]),
     "lc_status_string": (C.c_char_p, [_i]),
     "lc_version": (_i, []),
@@ -127,6 +132,31 @@ def lc_pbit_sum_apply(q, q_stride_bytes, in_bits, W, n, p, sum_out, step, tie_ru
     return _call("lc_pbit_sum_apply", check, _ptr(q), q_stride_bytes, in_bits, W, n, p, _ptr(sum_out), step,
                  tie_rule, _ptr(theta), lr, wd, _ptr(m), m_stride_elems, _ptr(g), g_stride_elems, g_dtype, n_m,
                  beta2, _stream(stream))
+
+
+def lc_l1_mean_abs(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, mean_abs, workspace, stream=None,
+                   check=True):
+    return _call("lc_l1_mean_abs", check, _ptr(g), g_stride_elems, g_dtype, _ptr(m), m_stride_elems, W, n, beta1,
+                 _ptr(mean_abs), _ptr(workspace), _stream(stream))
+
+
+def lc_l1_quantize_pack(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, update_m, beta2, levels, mean_abs,
+                        q, q_stride_bytes, stream=None, check=True):
+    return _call("lc_l1_quantize_pack", check, _ptr(g), g_stride_elems, g_dtype, _ptr(m), m_stride_elems, W, n, beta1,
+                 int(update_m), beta2, levels, _ptr(mean_abs), _ptr(q), q_stride_bytes, _stream(stream))
+
+
+def lc_level_sum_sign(q, q_stride_bytes, W, n, levels, sum_out, vote_pos, vote_nz, step, tie_rule, stream=None,
+                      check=True):
+    return _call("lc_level_sum_sign", check, _ptr(q), q_stride_bytes, W, n, levels, _ptr(sum_out), _ptr(vote_pos),
+                 _ptr(vote_nz), step, tie_rule, _stream(stream))
+
+
+def lc_level_sum_apply(q, q_stride_bytes, W, n, levels, sum_out, step, tie_rule, theta, lr, wd, m, m_stride_elems, g,
+                       g_stride_elems, g_dtype, n_m, beta2, stream=None, check=True):
+    return _call("lc_level_sum_apply", check, _ptr(q), q_stride_bytes, W, n, levels, _ptr(sum_out), step, tie_rule,
+                 _ptr(theta), lr, wd, _ptr(m), m_stride_elems, _ptr(g), g_stride_elems, g_dtype, n_m, beta2,
+                 _stream(stream))
 
 
 def lc_container_bits(p):

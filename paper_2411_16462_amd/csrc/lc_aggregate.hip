@@ -81,13 +81,13 @@ __device__ __forceinline__ void compare_planes(const uint64_t (&c)[8], int T, ui
     }
 }
 
-// From "K > W/2" and "K == W/2" to the two vote planes.  For odd W, K == floor(W/2)
-// means S = -1: not a tie.
-__device__ __forceinline__ void vote_planes(uint64_t gt, uint64_t eq, int W, int tie, uint64_t &pos, uint64_t &nz)
+// From "K > T" and "K == T" to the two vote planes.  K == T is a tie only if the
+// caller says so (for an odd number of 0/1 votes K == floor(W/2) means S = -1).
+__device__ __forceinline__ void vote_planes(uint64_t gt, uint64_t eq, bool tie_possible, int tie, uint64_t &pos, uint64_t &nz)
 {
     pos = gt;
     nz = ~0ull;
-    if ((W & 1) == 0) {
+    if (tie_possible) {
         if (tie < 0) nz = ~eq;
         else if (tie > 0) pos |= eq;
     }
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
     if (wave_base >= n) return;
     const bool full_wave = wave_base + kAggWave <= n;
     const int W = P.W;
-    const int T = W >> 1;
+    const int T = P.thresh;  // the count at which the sum of signs (or of levels) is zero
 
     // theta first: these loads overlap all of phase A
     f32x4 th[kAggTiles];
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
         for (int mask = kAggWords; mask < kWave; mask <<= 1) add_partner(c, lane, mask, np);
         uint64_t gt, eq, pos, nz;
         compare_planes(c, T, gt, eq);
-        vote_planes(gt, eq, W, P.tie, pos, nz);
+        vote_planes(gt, eq, P.tie_possible != 0, P.tie, pos, nz);
         pos &= vm;
         nz &= vm;
         if (ph == 0) {
@@ -337,7 +337,7 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
             eq |= static_cast<uint64_t>(K == static_cast<uint32_t>(T)) << f;
         }
         uint64_t pos, nz;
-        vote_planes(gt, eq, W, P.tie, pos, nz);
+        vote_planes(gt, eq, P.tie_possible != 0, P.tie, pos, nz);
         const uint64_t vm = valid_mask(e0, n) & ((1ull << kFpl) - 1ull);
         if constexpr (kFpl == 16) {
             reinterpret_cast<uint16_t *>(s_pos[wave])[lane] = static_cast<uint16_t>(pos & vm);

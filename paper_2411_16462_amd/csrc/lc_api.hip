@@ -34,14 +34,17 @@ int tie_code(int tie_rule, uint64_t step)
 }
 
 // shared by the four aggregation entry points
-int aggregate(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n, int p, void *sum_out, uint64_t *vote_pos,
+int aggregate(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n, int p, int levels, void *sum_out, uint64_t *vote_pos,
               uint64_t *vote_nz, uint64_t step, int tie_rule, bool apply, float *theta, float lr, float wd, float *m,
               size_t m_stride, const void *g, size_t g_stride, int g_dtype, int n_m, float beta2, void *stream)
 {
     if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
     if (tie_rule != LC_TIE_ZERO && tie_rule != LC_TIE_ALT) return LC_ERR_MODE;
     int sum_bits = 0;
-    if (p != 0) {  // p-bit sum: range rule of the direct allreduce
+    if (levels != 0) {  // summed level bytes: every row holds level + L in [0, 2L]
+        if (levels < 1 || levels > 127 || 2 * levels * W > 255) return LC_ERR_RANGE;
+        sum_bits = 8;
+    } else if (p != 0) {  // p-bit sum: range rule of the direct allreduce
         sum_bits = container(p);
         if (sum_bits < 0) return LC_ERR_RANGE;
         if (W > (1 << p) - 1) return LC_ERR_RANGE;
@@ -77,6 +80,8 @@ int aggregate(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n
     P.vote_pos = vote_pos;
     P.vote_nz = vote_nz;
     P.tie = tie_code(tie_rule, step);
+    P.thresh = levels > 0 ? W * levels : (W >> 1);
+    P.tie_possible = levels > 0 ? 1 : ((W & 1) == 0);
     P.theta = theta;
     P.lr = lr;
     P.wd = wd;
@@ -122,7 +127,7 @@ int lc_local_update_pack(const void *g, size_t g_stride_elems, int g_dtype, floa
 int lc_vote_1bit(const uint64_t *q, size_t q_stride_words, int W, size_t n, uint64_t *vote_pos, uint64_t *vote_nz,
                  uint64_t step, int tie_rule, void *stream)
 {
-    return aggregate(q, q_stride_words * 8, 1, W, n, 0, nullptr, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f, 0.0f,
+    return aggregate(q, q_stride_words * 8, 1, W, n, 0, 0, nullptr, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f, 0.0f,
                      nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream);
 }
 
@@ -130,7 +135,7 @@ int lc_pbit_sum_sign(const void *q, size_t q_stride_bytes, int in_bits, int W, s
                      uint64_t *vote_pos, uint64_t *vote_nz, uint64_t step, int tie_rule, void *stream)
 {
     if (p == 0) return LC_ERR_RANGE;
-    return aggregate(q, q_stride_bytes, in_bits, W, n, p, sum_out, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f,
+    return aggregate(q, q_stride_bytes, in_bits, W, n, p, 0, sum_out, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f,
                      0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream);
 }
 
@@ -138,7 +143,7 @@ int lc_vote_apply_1bit(const uint64_t *q, size_t q_stride_words, int W, size_t n
                        float lr, float wd, float *m, size_t m_stride_elems, const void *g, size_t g_stride_elems, int g_dtype,
                        int n_m, float beta2, void *stream)
 {
-    return aggregate(q, q_stride_words * 8, 1, W, n, 0, nullptr, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
+    return aggregate(q, q_stride_words * 8, 1, W, n, 0, 0, nullptr, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
                      m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
 }
 
@@ -147,7 +152,7 @@ int lc_pbit_sum_apply(const void *q, size_t q_stride_bytes, int in_bits, int W, 
                       size_t g_stride_elems, int g_dtype, int n_m, float beta2, void *stream)
 {
     if (p == 0) return LC_ERR_RANGE;
-    return aggregate(q, q_stride_bytes, in_bits, W, n, p, sum_out, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
+    return aggregate(q, q_stride_bytes, in_bits, W, n, p, 0, sum_out, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
                      m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
 }
 
@@ -169,6 +174,8 @@ int lc_apply_update(float *theta, const uint64_t *vote_pos, const uint64_t *vote
     P.in_pos = vote_pos;
     P.in_nz = vote_nz;
     P.tie = -1;
+    P.thresh = 0;
+    P.tie_possible = 0;
     P.theta = theta;
     P.lr = lr;
     P.wd = wd;
@@ -189,6 +196,50 @@ int lc_momentum_avg(float *m, size_t m_stride_elems, int W, size_t n, void *stre
     if (!aligned(m, 16) || (W > 1 && (m_stride_elems * 4) % 16 != 0)) return LC_ERR_ALIGN;
     if (n == 0 || W == 1) return LC_OK;
     return from_hip(launch_momentum_avg(m, m_stride_elems, W, n, static_cast<hipStream_t>(stream)));
+}
+
+int lc_l1_mean_abs(const void *g, size_t g_stride_elems, int g_dtype, const float *m, size_t m_stride_elems, int W, size_t n,
+                   float beta1, double *mean_abs, uint64_t *workspace, void *stream)
+{
+    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
+    if (rc) return rc;
+    if (!mean_abs || !workspace) return LC_ERR_NULL;
+    if (!aligned(mean_abs, 8) || !aligned(workspace, 8)) return LC_ERR_ALIGN;
+    return from_hip(launch_l1_mean_abs(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, mean_abs, workspace,
+                                       static_cast<hipStream_t>(stream)));
+}
+
+int lc_l1_quantize_pack(const void *g, size_t g_stride_elems, int g_dtype, float *m, size_t m_stride_elems, int W, size_t n,
+                        float beta1, int update_m, float beta2, int levels, const double *mean_abs, uint8_t *q,
+                        size_t q_stride_bytes, void *stream)
+{
+    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    if (levels < 1 || levels > 127) return LC_ERR_RANGE;
+    const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
+    if (rc) return rc;
+    if (!mean_abs || !q) return LC_ERR_NULL;
+    if (!aligned(mean_abs, 8) || !aligned(q, 16) || (W > 1 && q_stride_bytes % 16 != 0)) return LC_ERR_ALIGN;
+    if (n == 0) return LC_OK;
+    return from_hip(launch_l1_quantize_pack(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, update_m != 0, beta2,
+                                            levels, mean_abs, q, q_stride_bytes, static_cast<hipStream_t>(stream)));
+}
+
+int lc_level_sum_sign(const uint8_t *q, size_t q_stride_bytes, int W, size_t n, int levels, uint8_t *sum_out,
+                      uint64_t *vote_pos, uint64_t *vote_nz, uint64_t step, int tie_rule, void *stream)
+{
+    if (levels == 0) return LC_ERR_RANGE;
+    return aggregate(q, q_stride_bytes, 8, W, n, 0, levels, sum_out, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f,
+                     0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream);
+}
+
+int lc_level_sum_apply(const uint8_t *q, size_t q_stride_bytes, int W, size_t n, int levels, uint8_t *sum_out, uint64_t step,
+                       int tie_rule, float *theta, float lr, float wd, float *m, size_t m_stride_elems, const void *g,
+                       size_t g_stride_elems, int g_dtype, int n_m, float beta2, void *stream)
+{
+    if (levels == 0) return LC_ERR_RANGE;
+    return aggregate(q, q_stride_bytes, 8, W, n, 0, levels, sum_out, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
+                     m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
 }
 
 int lc_container_bits(int p) { return container(p); }

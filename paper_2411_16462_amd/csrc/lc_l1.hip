@@ -1,0 +1,307 @@
+// L1 quantisation of the update (Section 4.2, Equation 1 with p = 1; Appendix F.1):
+//   pass 1  M_1 = mean_i |c_i| per worker, with the sum formed WITHOUT rounding, so that the
+//           result does not depend on the order in which a GPU adds and equals what a
+//           sequential exact summation gives;
+//   pass 2  level_i = clamp(round(L / (2 M_1) * c_i), L), stored as the byte level_i + L,
+//           fused with the momentum update of Algorithm 1 line 6.
+// c = beta1 * m + (1 - beta1) * g as in the 1-bit path (same fixed fp32 evaluation).
+//
+// Exact sum.  A finite binary32 is an integer M < 2^24 times 2^(P-149), P = max(E, 1) - 1 the
+// bit position of M's lowest bit.  Integers add exactly, so the sum is kept as one long
+// integer in units of 2^-149: 64-bit accumulators 32 bits apart ("limbs"), each of which
+// only ever receives pieces below 2^32 and therefore cannot overflow for any n < 2^32
+// additions.  A wave reduces a 256-element tile to one 63-bit integer relative to the
+// tile's lowest P (possible whenever the tile's magnitudes span fewer than 32 binary
+// orders, else lanes add their elements one by one), adds it to the workgroup's limbs in
+// LDS; the workgroup adds its limbs, carries propagated, to the worker's limbs in global
+// memory with 64-bit atomics.  A one-thread kernel rounds the long integer once to fp64
+// (nearest, ties to even) and divides by n.
+#include "lc_launch.hpp"
+
+namespace lc {
+
+#ifndef LC_L1_TILES
+#define LC_L1_TILES 8
+#endif
+constexpr int kL1Threads = 256;
+constexpr int kL1Waves = kL1Threads / kWave;
+constexpr int kL1Tiles = LC_L1_TILES;                       // 256-element tiles per wave
+constexpr int kL1Block = kL1Waves * kL1Tiles * 256;         // elements per workgroup
+
+__device__ __forceinline__ float interpolate_c(float m, float g, float beta1, float omb1)
+{
+    return __builtin_fmaf(beta1, m, omb1 * g);
+}
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_mov(uint32_t v)
+{
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(static_cast<int>(v), static_cast<int>(v), CTRL, 0xF, 0xF, false));
+}
+
+// min and max over the wave, uniform result
+__device__ __forceinline__ void wave_min_max(uint32_t lo, uint32_t hi, uint32_t &wmin, uint32_t &wmax)
+{
+#define LC_STEP(CTRL)                          \
+    {                                          \
+        const uint32_t a = dpp_mov<CTRL>(lo);  \
+        const uint32_t b = dpp_mov<CTRL>(hi);  \
+        lo = a < lo ? a : lo;                  \
+        hi = b > hi ? b : hi;                  \
+    }
+    LC_STEP(0xB1)   // quad_perm [1,0,3,2]
+    LC_STEP(0x4E)   // quad_perm [2,3,0,1]
+    LC_STEP(0x141)  // row_half_mirror
+    LC_STEP(0x140)  // row_mirror: every lane of a row of 16 now holds the row's result
+#undef LC_STEP
+    uint32_t a0 = __builtin_amdgcn_readlane(lo, 0), a1 = __builtin_amdgcn_readlane(lo, 16);
+    uint32_t a2 = __builtin_amdgcn_readlane(lo, 32), a3 = __builtin_amdgcn_readlane(lo, 48);
+    uint32_t b0 = __builtin_amdgcn_readlane(hi, 0), b1 = __builtin_amdgcn_readlane(hi, 16);
+    uint32_t b2 = __builtin_amdgcn_readlane(hi, 32), b3 = __builtin_amdgcn_readlane(hi, 48);
+    a0 = a0 < a1 ? a0 : a1;
+    a2 = a2 < a3 ? a2 : a3;
+    b0 = b0 > b1 ? b0 : b1;
+    b2 = b2 > b3 ? b2 : b3;
+    wmin = a0 < a2 ? a0 : a2;
+    wmax = b0 > b2 ? b0 : b2;
+}
+
+__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v, int lane)
+{
+#pragma unroll
+    for (int mask = 1; mask < kWave; mask <<= 1) {
+        const int addr = (lane ^ mask) << 2;
+        const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(addr, static_cast<int>(static_cast<uint32_t>(v))));
+        const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(addr, static_cast<int>(static_cast<uint32_t>(v >> 32))));
+        v += (static_cast<uint64_t>(hi) << 32) | lo;
+    }
+    return v;
+}
+
+// value << pos added to the limbs (pieces of 32 bits)
+__device__ __forceinline__ void limbs_add(uint64_t *limbs, uint64_t value, uint32_t pos)
+{
+    const uint32_t l = pos >> 5, sh = pos & 31u;
+    const unsigned __int128 v = static_cast<unsigned __int128>(value) << sh;
+    const uint64_t p0 = static_cast<uint64_t>(v) & 0xFFFFFFFFull;
+    const uint64_t p1 = static_cast<uint64_t>(v >> 32) & 0xFFFFFFFFull;
+    const uint64_t p2 = static_cast<uint64_t>(v >> 64);
+    if (p0) atomicAdd(reinterpret_cast<unsigned long long *>(limbs + l), static_cast<unsigned long long>(p0));
+    if (p1) atomicAdd(reinterpret_cast<unsigned long long *>(limbs + l + 1), static_cast<unsigned long long>(p1));
+    if (p2) atomicAdd(reinterpret_cast<unsigned long long *>(limbs + l + 2), static_cast<unsigned long long>(p2));
+}
+
+__global__ void l1_zero_kernel(uint64_t *workspace, int words)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < words) workspace[i] = 0;
+}
+
+template <int GDT>
+__global__ __launch_bounds__(kL1Threads) void l1_abs_sum_kernel(const void *__restrict__ g, size_t g_stride,
+                                                                const float *__restrict__ m, size_t m_stride, size_t n,
+                                                                float beta1, float omb1, uint64_t *__restrict__ workspace)
+{
+    __shared__ uint64_t s_limbs[kL1Limbs];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const size_t w = blockIdx.y;
+    if (threadIdx.x < kL1Limbs) s_limbs[threadIdx.x] = 0;
+    __syncthreads();
+
+    const float *mrow = m + w * m_stride;
+    const void *grow = static_cast<const char *>(g) + w * g_stride * Grad<GDT>::kBytes;
+    const size_t wave_base = static_cast<size_t>(blockIdx.x) * kL1Block + static_cast<size_t>(wave) * (kL1Tiles * 256);
+
+#pragma unroll 2
+    for (int t = 0; t < kL1Tiles; ++t) {
+        const size_t tile = wave_base + static_cast<size_t>(t) * 256;
+        if (tile >= n) break;  // uniform in the wave
+        const size_t e = tile + lane * 4;
+        f32x4 mv = {0.0f, 0.0f, 0.0f, 0.0f}, gv = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (e + 4 <= n) {
+            mv = ld_grad(reinterpret_cast<const f32x4 *>(mrow + e));
+            gv = Grad<GDT>::load4(grow, e);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (e + k < n) {
+                    mv[k] = mrow[e + k];
+                    gv[k] = Grad<GDT>::load1(grow, e + k);
+                }
+        }
+        uint32_t mant[4], pos[4];
+        uint32_t pmin = 0xFFFFu, pmax = 0u;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t b = __float_as_uint(interpolate_c(mv[k], gv[k], beta1, omb1)) & 0x7FFFFFFFu;
+            const uint32_t ex = b >> 23;
+            mant[k] = ex ? ((b & 0x7FFFFFu) | 0x800000u) : b;
+            pos[k] = ex ? ex - 1u : 0u;
+            if (mant[k]) {
+                pmin = pos[k] < pmin ? pos[k] : pmin;
+                pmax = pos[k] > pmax ? pos[k] : pmax;
+            }
+        }
+        uint32_t wmin, wmax;
+        wave_min_max(pmin, pmax, wmin, wmax);
+        if (wmin == 0xFFFFu) continue;  // the whole tile is zero
+        if (wmax - wmin <= 31u) {
+            uint64_t tsum = 0;          // < 4 * 2^55 per lane, < 2^63 per wave
+#pragma unroll
+            for (int k = 0; k < 4; ++k) tsum += static_cast<uint64_t>(mant[k]) << (mant[k] ? pos[k] - wmin : 0u);
+            tsum = wave_sum_u64(tsum, lane);
+            if (lane == 0) limbs_add(s_limbs, tsum, wmin);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (mant[k]) limbs_add(s_limbs, mant[k], pos[k]);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t carry = 0;
+        uint64_t *dst = workspace + w * kL1Limbs;
+#pragma unroll
+        for (int l = 0; l < kL1Limbs; ++l) {
+            const uint64_t v = s_limbs[l] + carry;
+            const uint64_t piece = v & 0xFFFFFFFFull;
+            carry = v >> 32;
+            if (piece) atomicAdd(reinterpret_cast<unsigned long long *>(dst + l), static_cast<unsigned long long>(piece));
+        }
+    }
+}
+
+// One thread per worker: the limbs as one integer (units of 2^-149), rounded once to
+// fp64 (nearest, ties to even), divided by n.
+__global__ void l1_finalize_kernel(uint64_t *workspace, int W, size_t n, double *mean_abs)
+{
+    const int w = blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= W) return;
+    uint64_t *limb = workspace + static_cast<size_t>(w) * kL1Limbs;
+    uint64_t carry = 0;
+    int top = -1;
+    for (int l = 0; l < kL1Limbs; ++l) {  // after this every limb is below 2^32
+        const uint64_t v = limb[l] + carry;
+        limb[l] = v & 0xFFFFFFFFull;
+        carry = v >> 32;
+        if (limb[l]) top = l;
+    }
+    double sum = 0.0;
+    if (top >= 0) {
+        const int tb = 32 * top + (31 - __builtin_clz(static_cast<uint32_t>(limb[top])));  // index of the highest set bit
+        if (tb <= 52) {
+            sum = static_cast<double>(limb[0] | (limb[1] << 32));
+        } else {
+            const int shift = tb - 52;  // bits below `shift` are rounded away
+            const int li = shift >> 5, off = shift & 31;
+            unsigned __int128 window = static_cast<unsigned __int128>(limb[li]);
+            if (li + 1 < kL1Limbs) window |= static_cast<unsigned __int128>(limb[li + 1]) << 32;
+            if (li + 2 < kL1Limbs) window |= static_cast<unsigned __int128>(limb[li + 2]) << 64;
+            uint64_t mant = static_cast<uint64_t>(window >> off) & ((1ull << 53) - 1ull);
+            const int rb = shift - 1;
+            const bool round_bit = (limb[rb >> 5] >> (rb & 31)) & 1ull;
+            bool sticky = false;
+            for (int l = 0; l <= (rb >> 5); ++l) {
+                uint64_t v = limb[l];
+                if (l == (rb >> 5)) v &= (1ull << (rb & 31)) - 1ull;
+                sticky = sticky || v != 0;
+            }
+            if (round_bit && (sticky || (mant & 1ull))) mant += 1;
+            sum = ldexp(static_cast<double>(mant), shift);
+        }
+        sum = ldexp(sum, -149);
+    }
+    mean_abs[w] = n ? sum / static_cast<double>(n) : 0.0;
+}
+
+hipError_t launch_l1_mean_abs(const void *g, size_t g_stride, int g_dtype, const float *m, size_t m_stride, int W, size_t n,
+                              float beta1, double *mean_abs, uint64_t *workspace, hipStream_t s)
+{
+    const int words = W * kL1Limbs;
+    l1_zero_kernel<<<(words + 255) / 256, 256, 0, s>>>(workspace, words);
+    if (n > 0) {
+        const dim3 grid(static_cast<unsigned>((n + kL1Block - 1) / kL1Block), static_cast<unsigned>(W));
+        const float omb1 = 1.0f - beta1;
+        if (g_dtype == LC_BF16)
+            l1_abs_sum_kernel<LC_BF16><<<grid, kL1Threads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, workspace);
+        else
+            l1_abs_sum_kernel<LC_F32><<<grid, kL1Threads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, workspace);
+    }
+    l1_finalize_kernel<<<(W + 63) / 64, 64, 0, s>>>(workspace, W, n, mean_abs);
+    return hipGetLastError();
+}
+
+// ---- pass 2: levels --------------------------------------------------------------------
+constexpr int kQuantThreads = 64;  // one wave, one 256-element tile: same shape as the 1-bit pack kernel
+
+template <int GDT, bool UPDATE_M>
+__global__ __launch_bounds__(kQuantThreads) void l1_quantize_pack_kernel(const void *__restrict__ g, size_t g_stride,
+                                                                         float *__restrict__ m, size_t m_stride, size_t n,
+                                                                         float beta1, float omb1, float beta2, float omb2,
+                                                                         int L, const double *__restrict__ mean_abs,
+                                                                         uint8_t *__restrict__ q, size_t q_stride_bytes)
+{
+    const int lane = threadIdx.x;
+    const size_t w = blockIdx.y;
+    const size_t e = static_cast<size_t>(blockIdx.x) * 256 + lane * 4;
+    if (e >= n) return;
+    const double mean = mean_abs[w];
+    const bool live = mean > 0.0;                       // all-zero input: every level is 0
+    const float scale = live ? static_cast<float>(static_cast<double>(L) / (2.0 * mean)) : 0.0f;
+    const float fl = static_cast<float>(L);
+    float *mrow = m + w * m_stride;
+    const void *grow = static_cast<const char *>(g) + w * g_stride * Grad<GDT>::kBytes;
+    uint8_t *qrow = q + w * q_stride_bytes;
+    if (e + 4 <= n) {
+        f32x4 mv = load4(mrow + e);
+        const f32x4 gv = Grad<GDT>::load4(grow, e);
+        uint32_t bytes = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float c = interpolate_c(mv[k], gv[k], beta1, omb1);
+            float r = __builtin_rintf(scale * c);
+            r = r > fl ? fl : r;
+            r = r < -fl ? -fl : r;
+            const int level = live ? static_cast<int>(r) : 0;
+            bytes |= static_cast<uint32_t>(level + L) << (8 * k);
+            if (UPDATE_M) mv[k] = momentum_step(mv[k], gv[k], beta2, omb2);
+        }
+        if (UPDATE_M) store4(mrow + e, mv);
+        st_stream(reinterpret_cast<uint32_t *>(qrow + e), bytes);
+    } else {
+        for (int k = 0; k < 4 && e + k < n; ++k) {
+            const float mm = mrow[e + k];
+            const float gg = Grad<GDT>::load1(grow, e + k);
+            const float c = interpolate_c(mm, gg, beta1, omb1);
+            float r = __builtin_rintf(scale * c);
+            r = r > fl ? fl : r;
+            r = r < -fl ? -fl : r;
+            const int level = live ? static_cast<int>(r) : 0;
+            qrow[e + k] = static_cast<uint8_t>(level + L);
+            if (UPDATE_M) mrow[e + k] = momentum_step(mm, gg, beta2, omb2);
+        }
+    }
+}
+
+hipError_t launch_l1_quantize_pack(const void *g, size_t g_stride, int g_dtype, float *m, size_t m_stride, int W, size_t n,
+                                   float beta1, bool update_m, float beta2, int levels, const double *mean_abs, uint8_t *q,
+                                   size_t q_stride_bytes, hipStream_t s)
+{
+    const dim3 grid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(W));
+    const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+#define LC_LAUNCH(GDT, UPD)                                                                                                  \
+    l1_quantize_pack_kernel<GDT, UPD><<<grid, kQuantThreads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, beta2, omb2, \
+                                                                     levels, mean_abs, q, q_stride_bytes)
+    if (g_dtype == LC_BF16) {
+        if (update_m) LC_LAUNCH(LC_BF16, true);
+        else LC_LAUNCH(LC_BF16, false);
+    } else {
+        if (update_m) LC_LAUNCH(LC_F32, true);
+        else LC_LAUNCH(LC_F32, false);
+    }
+#undef LC_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace lc

@@ -18,6 +18,8 @@ struct AggParams {
     const uint64_t *in_pos; // IN_PLANES only
     const uint64_t *in_nz;  // IN_PLANES only; null = every element non-zero
     int tie;                // -1: tie -> 0 ; 0: tie -> -1 ; +1: tie -> +1
+    int thresh;             // count K at which the summed signs / levels are zero
+    int tie_possible;       // K == thresh is a tie (even W for 0/1 votes; always for levels)
     float *theta;
     float lr, wd;
     float *m;
@@ -35,5 +37,13 @@ hipError_t launch_local_update_pack(const void *g, size_t g_stride, int g_dtype,
 // kout: the counts K are wanted as fields from 1-bit rows.
 hipError_t launch_aggregate(const AggParams &P, int in_kind, bool apply, bool kout, int g_dtype, hipStream_t s);
 hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStream_t s);
+
+// L1 quantisation (Equation 1, p = 1)
+constexpr int kL1Limbs = 12;  // 64-bit accumulators, 32 bits apart, per worker
+hipError_t launch_l1_mean_abs(const void *g, size_t g_stride, int g_dtype, const float *m, size_t m_stride, int W, size_t n,
+                              float beta1, double *mean_abs, uint64_t *workspace, hipStream_t s);
+hipError_t launch_l1_quantize_pack(const void *g, size_t g_stride, int g_dtype, float *m, size_t m_stride, int W, size_t n,
+                                   float beta1, bool update_m, float beta2, int levels, const double *mean_abs, uint8_t *q,
+                                   size_t q_stride_bytes, hipStream_t s);
 
 }  // namespace lc

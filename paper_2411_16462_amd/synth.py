@@ -48,8 +48,10 @@ class Workload:
     name: str
     n: int                      # parameters in the flat arena
     W: int                      # simulated workers
-    mode: str                   # "1bit" | "pbit" | "prepacked"
+    mode: str                   # "1bit" | "pbit" | "prepacked" | "l1"
     p: int = 1                  # bits per summed field (pbit / prepacked-sum)
+    levels: int = 0             # l1: levels on each side of zero (L = 15: Appendix F.1's 8-bit case)
+    dist: str = "normal"        # gradient noise: "normal" | "laplace" (Section 4.1: updates look Laplacian)
     g_dtype: str = "f32"        # "f32" | "bf16"
     noise: float = 1.0          # g_w = s + noise * e_w
     m_spread: float = 0.05
@@ -77,6 +79,10 @@ def workloads() -> List[Workload]:
                  momentum_avg=True, tensors=medium, seed=0x11C3),
         Workload("c4_1p3b_w64_prepacked", 1_300_000_000, 64, "prepacked", p=7,
                  seed=0x11C4),
+        # beyond the five benchmark configurations: the paper's 8-bit L1-quantised allreduce
+        # among 8 workers (Appendix F.1), levels in [-15, 15], on the GPT-2-small shapes
+        Workload("l1_gpt2s_w8_l15", n_small, 8, "l1", levels=15, dist="laplace", tensors=small,
+                 seed=0x11C5),
     ]
 
 
@@ -102,9 +108,17 @@ def _rows(W: int, n: int, dtype, device) -> torch.Tensor:
     return torch.zeros((W, stride), dtype=dtype, device=device)[:, :n]
 
 
+def _noise(n, gen, device, dist):
+    if dist == "laplace":      # unit-variance Laplace by inverting its distribution function
+        u = torch.rand(n, generator=gen, device=device) - 0.5
+        return -torch.sign(u) * torch.log1p(-2.0 * u.abs().clamp(max=0.4999999)) * (0.5 ** 0.5)
+    return torch.randn(n, generator=gen, device=device)
+
+
 def make_state(n: int, W: int, *, seed: int, device="cpu", g_dtype: str = "f32",
                noise: float = 1.0, m_spread: float = 0.05, m_scale: float = 1e-3,
-               g_scale: float = 1e-3, with_theta: bool = True, with_m: bool = True):
+               g_scale: float = 1e-3, with_theta: bool = True, with_m: bool = True,
+               dist: str = "normal"):
     """theta (n,), m (W, n) fp32 and g (W, n) fp32 or bf16, drawn as the module
     docstring states.  bf16 gradients are the fp32 draw rounded to nearest-even."""
     gen = _gen(device, seed)
@@ -117,10 +131,10 @@ def make_state(n: int, W: int, *, seed: int, device="cpu", g_dtype: str = "f32",
         for w in range(W):
             m[w] = m0 + (m_spread * m_scale) * torch.randn(n, generator=gen, device=device)
         out["m"] = m
-    s = torch.randn(n, generator=gen, device=device) * g_scale
+    s = _noise(n, gen, device, dist) * g_scale
     g = _rows(W, n, torch.bfloat16 if g_dtype == "bf16" else torch.float32, device)
     for w in range(W):
-        gw = s + (noise * g_scale) * torch.randn(n, generator=gen, device=device)
+        gw = s + (noise * g_scale) * _noise(n, gen, device, dist)
         g[w] = gw.to(g.dtype)
     out["g"] = g
     return out

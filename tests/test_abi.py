@@ -139,3 +139,33 @@ def test_apply_avg_and_fused_validation():
     assert lc.lc_pbit_sum_apply(**pa) == lc.LC_OK
     assert lc.lc_pbit_sum_apply(**{**pa, "W": 16}) == lc.LC_ERR_RANGE
     assert lc.lc_pbit_sum_apply(**{**pa, "theta": None}) == lc.LC_ERR_NULL
+
+
+def test_l1_validation():
+    mean = dict(g=A, g_stride_elems=1024, g_dtype=lc.LC_F32, m=A, m_stride_elems=1024, W=4, n=0, beta1=0.9, mean_abs=A,
+                workspace=A, stream=0, check=False)
+    assert lc.lc_l1_mean_abs(**{**mean, "W": 0}) == lc.LC_ERR_SIZE
+    assert lc.lc_l1_mean_abs(**{**mean, "mean_abs": None}) == lc.LC_ERR_NULL
+    assert lc.lc_l1_mean_abs(**{**mean, "workspace": None}) == lc.LC_ERR_NULL
+    assert lc.lc_l1_mean_abs(**{**mean, "workspace": A + 4}) == lc.LC_ERR_ALIGN
+    assert lc.lc_l1_mean_abs(**{**mean, "g_dtype": 3}) == lc.LC_ERR_DTYPE
+    qz = dict(g=A, g_stride_elems=1024, g_dtype=lc.LC_F32, m=A, m_stride_elems=1024, W=4, n=0, beta1=0.9, update_m=1,
+              beta2=0.99, levels=15, mean_abs=A, q=A, q_stride_bytes=1024, stream=0, check=False)
+    assert lc.lc_l1_quantize_pack(**qz) == lc.LC_OK
+    assert lc.lc_l1_quantize_pack(**{**qz, "levels": 0}) == lc.LC_ERR_RANGE
+    assert lc.lc_l1_quantize_pack(**{**qz, "levels": 128}) == lc.LC_ERR_RANGE
+    assert lc.lc_l1_quantize_pack(**{**qz, "q": None}) == lc.LC_ERR_NULL
+    assert lc.lc_l1_quantize_pack(**{**qz, "q_stride_bytes": 1000}) == lc.LC_ERR_ALIGN
+    sm = dict(q=A, q_stride_bytes=1024, W=8, n=0, levels=15, sum_out=A, vote_pos=A, vote_nz=A, step=1,
+              tie_rule=lc.LC_TIE_ZERO, stream=0, check=False)
+    assert lc.lc_level_sum_sign(**sm) == lc.LC_OK                       # 8 workers x 30 = 240 fits a byte
+    assert lc.lc_level_sum_sign(**{**sm, "W": 9}) == lc.LC_ERR_RANGE    # 270 does not
+    assert lc.lc_level_sum_sign(**{**sm, "levels": 127, "W": 1}) == lc.LC_OK
+    assert lc.lc_level_sum_sign(**{**sm, "levels": 127, "W": 2}) == lc.LC_ERR_RANGE
+    assert lc.lc_level_sum_sign(**{**sm, "levels": 0}) == lc.LC_ERR_RANGE
+    ap = dict(q=A, q_stride_bytes=1024, W=8, n=0, levels=15, sum_out=None, step=1, tie_rule=lc.LC_TIE_ZERO, theta=A,
+              lr=1e-4, wd=0.1, m=None, m_stride_elems=0, g=None, g_stride_elems=0, g_dtype=lc.LC_F32, n_m=0, beta2=0.99,
+              stream=0, check=False)
+    assert lc.lc_level_sum_apply(**ap) == lc.LC_OK
+    assert lc.lc_level_sum_apply(**{**ap, "theta": None}) == lc.LC_ERR_NULL
+    assert lc.lc_level_sum_apply(**{**ap, "W": 9}) == lc.LC_ERR_RANGE
