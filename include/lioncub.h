@@ -137,7 +137,7 @@ int lc_pbit_sum_apply(const void *q, size_t q_stride_bytes, int in_bits, int W, 
  * are added as integers, which needs 2 L W <= 255 (else LC_ERR_RANGE); the update is the
  * sign of the summed levels, S = K - W L. */
 
-#define LC_L1_WORKSPACE_WORDS 12 /* uint64 words of device workspace per worker */
+#define LC_L1_WORKSPACE_WORDS 384 /* uint64 words of device workspace per worker */
 
 /* First pass: mean_abs[w] = M_1(c_w), fp64.  The sum of |c| is formed without rounding
  * (as a long integer, whatever the order of the additions), rounded once to fp64 and

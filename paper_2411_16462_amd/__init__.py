@@ -18,7 +18,7 @@ LC_F32, LC_BF16 = 0, 1
 LC_ZERO_ALT, LC_ZERO_POS, LC_ZERO_NEG = 0, 1, 2
 LC_TIE_ZERO, LC_TIE_ALT = 0, 1
 LC_MAX_W = 255
-LC_L1_WORKSPACE_WORDS = 12
+LC_L1_WORKSPACE_WORDS = 384
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblioncub.so")
 

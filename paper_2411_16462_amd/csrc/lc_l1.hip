@@ -10,11 +10,12 @@
 // bit position of M's lowest bit.  Integers add exactly, so the sum is kept as one long
 // integer in units of 2^-149: 64-bit accumulators 32 bits apart ("limbs"), each of which
 // only ever receives pieces below 2^32 and therefore cannot overflow for any n < 2^32
-// additions.  A wave reduces a 256-element tile to one 63-bit integer relative to the
-// tile's lowest P (possible whenever the tile's magnitudes span fewer than 32 binary
-// orders, else lanes add their elements one by one), adds it to the workgroup's limbs in
-// LDS; the workgroup adds its limbs, carries propagated, to the worker's limbs in global
-// memory with 64-bit atomics.  A one-thread kernel rounds the long integer once to fp64
+// additions.  Each lane of a wave sums its elements as 64-bit integers relative to a base
+// position chosen from the wave's first tile (elements whose magnitude lies outside a
+// window of 28 binary orders above that base -- rare -- go to the limbs one by one); the
+// wave adds its 64 lane sums, shifts the total to the base and adds it to the workgroup's
+// limbs in LDS; the workgroup adds its limbs, carries propagated, to the worker's limbs
+// in global memory with 64-bit atomics.  A one-thread kernel rounds the long integer once to fp64
 // (nearest, ties to even) and divides by n.
 #include "lc_launch.hpp"
 
@@ -97,6 +98,12 @@ __global__ void l1_zero_kernel(uint64_t *workspace, int words)
     if (i < words) workspace[i] = 0;
 }
 
+// How far above the wave's base position a magnitude may sit to take the fast path: a
+// lane then adds at most kL1Tiles * 4 integers below 2^(24 + kL1Window) to its private
+// 64-bit sum, and 64 such sums still fit 64 bits.
+constexpr uint32_t kL1Window = 28;
+static_assert(kL1Tiles * 4 <= 32, "lane sums must stay below 2^57");
+
 template <int GDT>
 __global__ __launch_bounds__(kL1Threads) void l1_abs_sum_kernel(const void *__restrict__ g, size_t g_stride,
                                                                 const float *__restrict__ m, size_t m_stride, size_t n,
@@ -113,6 +120,12 @@ __global__ __launch_bounds__(kL1Threads) void l1_abs_sum_kernel(const void *__re
     const void *grow = static_cast<const char *>(g) + w * g_stride * Grad<GDT>::kBytes;
     const size_t wave_base = static_cast<size_t>(blockIdx.x) * kL1Block + static_cast<size_t>(wave) * (kL1Tiles * 256);
 
+    // The wave's base position comes from its first tile: 22 binary orders below that
+    // tile's largest magnitude, so the window reaches 64 times above it.  Elements outside
+    // the window (tiny or huge against the rest) go to the limbs one by one: still exact.
+    uint32_t base = 0;
+    uint64_t lane_sum = 0;
+    bool have_base = false;
 #pragma unroll 2
     for (int t = 0; t < kL1Tiles; ++t) {
         const size_t tile = wave_base + static_cast<size_t>(t) * 256;
@@ -131,37 +144,47 @@ __global__ __launch_bounds__(kL1Threads) void l1_abs_sum_kernel(const void *__re
                 }
         }
         uint32_t mant[4], pos[4];
-        uint32_t pmin = 0xFFFFu, pmax = 0u;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const uint32_t b = __float_as_uint(interpolate_c(mv[k], gv[k], beta1, omb1)) & 0x7FFFFFFFu;
             const uint32_t ex = b >> 23;
             mant[k] = ex ? ((b & 0x7FFFFFu) | 0x800000u) : b;
             pos[k] = ex ? ex - 1u : 0u;
-            if (mant[k]) {
-                pmin = pos[k] < pmin ? pos[k] : pmin;
-                pmax = pos[k] > pmax ? pos[k] : pmax;
-            }
         }
-        uint32_t wmin, wmax;
-        wave_min_max(pmin, pmax, wmin, wmax);
-        if (wmin == 0xFFFFu) continue;  // the whole tile is zero
-        if (wmax - wmin <= 31u) {
-            uint64_t tsum = 0;          // < 4 * 2^55 per lane, < 2^63 per wave
-#pragma unroll
-            for (int k = 0; k < 4; ++k) tsum += static_cast<uint64_t>(mant[k]) << (mant[k] ? pos[k] - wmin : 0u);
-            tsum = wave_sum_u64(tsum, lane);
-            if (lane == 0) limbs_add(s_limbs, tsum, wmin);
-        } else {
+        if (!have_base) {  // uniform
+            uint32_t pmin = 0xFFFFu, pmax = 0u;
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-                if (mant[k]) limbs_add(s_limbs, mant[k], pos[k]);
+                if (mant[k]) {
+                    pmin = pos[k] < pmin ? pos[k] : pmin;
+                    pmax = pos[k] > pmax ? pos[k] : pmax;
+                }
+            uint32_t wmin, wmax;
+            wave_min_max(pmin, pmax, wmin, wmax);
+            if (wmin == 0xFFFFu) continue;  // the whole tile is zero: nothing to add, no base yet
+            base = wmax > 22u ? wmax - 22u : 0u;
+            have_base = true;
         }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t rel = pos[k] - base;  // wraps for positions below the base
+            if (rel <= kL1Window || mant[k] == 0u) {
+                lane_sum += static_cast<uint64_t>(mant[k]) << (rel & 31u);
+            } else {
+                limbs_add(s_limbs, mant[k], pos[k]);
+            }
+        }
+    }
+    if (have_base) {
+        const uint64_t total = wave_sum_u64(lane_sum, lane);
+        if (lane == 0 && total) limbs_add(s_limbs, total, base);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
+        // one of kL1Slots accumulators per worker, so that the atomics of neighbouring
+        // workgroups do not queue on the same addresses
         uint64_t carry = 0;
-        uint64_t *dst = workspace + w * kL1Limbs;
+        uint64_t *dst = workspace + (w * kL1Slots + blockIdx.x % kL1Slots) * kL1Limbs;
 #pragma unroll
         for (int l = 0; l < kL1Limbs; ++l) {
             const uint64_t v = s_limbs[l] + carry;
@@ -178,7 +201,9 @@ __global__ void l1_finalize_kernel(uint64_t *workspace, int W, size_t n, double 
 {
     const int w = blockIdx.x * blockDim.x + threadIdx.x;
     if (w >= W) return;
-    uint64_t *limb = workspace + static_cast<size_t>(w) * kL1Limbs;
+    uint64_t *limb = workspace + static_cast<size_t>(w) * kL1Slots * kL1Limbs;  // slot 0 receives the total
+    for (int s = 1; s < kL1Slots; ++s)
+        for (int l = 0; l < kL1Limbs; ++l) limb[l] += limb[s * kL1Limbs + l];
     uint64_t carry = 0;
     int top = -1;
     for (int l = 0; l < kL1Limbs; ++l) {  // after this every limb is below 2^32
@@ -218,7 +243,7 @@ __global__ void l1_finalize_kernel(uint64_t *workspace, int W, size_t n, double 
 hipError_t launch_l1_mean_abs(const void *g, size_t g_stride, int g_dtype, const float *m, size_t m_stride, int W, size_t n,
                               float beta1, double *mean_abs, uint64_t *workspace, hipStream_t s)
 {
-    const int words = W * kL1Limbs;
+    const int words = W * kL1Slots * kL1Limbs;
     l1_zero_kernel<<<(words + 255) / 256, 256, 0, s>>>(workspace, words);
     if (n > 0) {
         const dim3 grid(static_cast<unsigned>((n + kL1Block - 1) / kL1Block), static_cast<unsigned>(W));

@@ -39,7 +39,9 @@ hipError_t launch_aggregate(const AggParams &P, int in_kind, bool apply, bool ko
 hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStream_t s);
 
 // L1 quantisation (Equation 1, p = 1)
-constexpr int kL1Limbs = 12;  // 64-bit accumulators, 32 bits apart, per worker
+constexpr int kL1Limbs = 12;  // 64-bit accumulators, 32 bits apart
+constexpr int kL1Slots = 32;  // independent sets of limbs per worker (spreads the atomics)
+static_assert(kL1Limbs * kL1Slots == LC_L1_WORKSPACE_WORDS, "workspace size in the header");
 hipError_t launch_l1_mean_abs(const void *g, size_t g_stride, int g_dtype, const float *m, size_t m_stride, int W, size_t n,
                               float beta1, double *mean_abs, uint64_t *workspace, hipStream_t s);
 hipError_t launch_l1_quantize_pack(const void *g, size_t g_stride, int g_dtype, float *m, size_t m_stride, int W, size_t n,

@@ -40,6 +40,7 @@ def test_binding_constants_match_header():
         m = re.search(r"\b%s\s*=\s*(\d+)" % name, text)
         assert m and int(m.group(1)) == getattr(lc, name), name
     assert int(re.search(r"#define LC_MAX_W (\d+)", text).group(1)) == lc.LC_MAX_W
+    assert int(re.search(r"#define LC_L1_WORKSPACE_WORDS (\d+)", text).group(1)) == lc.LC_L1_WORKSPACE_WORDS
 
 
 def test_version_status_strings_and_container_rule():

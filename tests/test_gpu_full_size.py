@@ -146,3 +146,40 @@ def test_reduction_only_workload():
     # agreement 0.6 with a shared latent sign: few ties, and the vote follows the latent bit
     tie_rate = float((u_all == 0).float().mean())
     assert 0.0 < tie_rate < 0.05
+
+
+def test_l1_workload():
+    """GPT-2-small shapes, 8 workers, L = 15 (the 8-bit L1-quantised allreduce of
+    Appendix F.1) as bench.py runs it.  The mean |c| of every worker is compared over
+    ALL elements (it must equal the oracle's exactly); levels, sums, theta and momenta on
+    sampled windows."""
+    wl = synth.workload("l1")
+    kernels, st, step_no = bench.build_step(wl, torch, lc, synth)
+    n, W, L = wl.n, wl.W, wl.levels
+    theta0 = st["theta"].clone()
+    m0 = torch.empty((W, n), dtype=torch.float32, device="cuda")
+    m0.copy_(st["m"])
+    for k in kernels:
+        k.fn()
+    torch.cuda.synchronize()
+    means = st["mean_abs"].cpu().numpy()
+    for w in range(W):
+        c = orc.local_c(m0[w].cpu().numpy(), st["g"][w].cpu().numpy(), wl.beta1)
+        assert orc.mean_abs(c) == means[w], "worker %d: mean |c| over all %d elements" % (w, n)
+        del c
+    for lo, hi in windows(n, wl.seed):
+        mm, gg = host_rows(m0, lo, hi), host_rows(st["g"], lo, hi)
+        lev = np.stack([orc.l1_levels(orc.local_c(mm[w], gg[w], wl.beta1), means[w], L) for w in range(W)])
+        fields = (lev.astype(np.int16) + L).astype(np.uint8)
+        assert np.array_equal(st["q"][:, lo:hi].cpu().numpy(), fields), "level bytes in [%d, %d)" % (lo, hi)
+        K, S, u = orc.level_sum_sign(fields, L, step_no[0], orc.TIE_ZERO)
+        assert np.array_equal(st["sum_out"][lo:hi].cpu().numpy().astype(np.int32), K)
+        assert_close(st["theta"][lo:hi].cpu().numpy(), orc.apply(theta0[lo:hi].cpu().numpy(), u, wl.lr, wl.wd), "theta")
+        m_ref = np.stack([orc.momentum(mm[w], gg[w], wl.beta2) for w in range(W)])
+        assert_close(host_rows(st["m"], lo, hi), m_ref, "momentum")
+    # whole range: the applied update is the sign of (summed bytes - W L)
+    K_all = st["sum_out"][:n].to(torch.int16)
+    u_all = torch.sign(K_all - W * L).to(torch.float32)
+    d = (st["theta"] - theta0 * (1.0 - wl.lr * wl.wd)) / wl.lr + u_all
+    assert float(d.abs().max()) < 1e-2 and int(K_all.max()) <= 2 * L * W
+    assert int(st["q"][:, :n].max()) <= 2 * L
