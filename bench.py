@@ -8,7 +8,7 @@ ABI of liblioncub.so.  Prints ONE JSON line: params/s for the step, the roofline
 dominant kernel (algorithmic bytes / its mean launch duration from HIP events on the
 launch stream) and the CPU oracle timed on a bounded sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c0|c2|c3|c4|l1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c0|c2|c3|c4|l1|t2]
 """
 import argparse
 import json
@@ -120,6 +120,20 @@ def build_step(wl, torch, lc, synth, per_tensor=False):
             lambda: lc.lc_vote_apply_1bit(q, q.stride(0), W, n, step_no[0], lc.LC_TIE_ZERO, theta, hp["lr"], hp["wd"],
                                           None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
             n * (W / 8 + 8)))
+    elif wl.mode == "ternary":
+        pos = torch.zeros((W, synth.round_up(nw, 8)), dtype=torch.int64, device=dev)
+        nz = torch.zeros((W, synth.round_up(nw, 8)), dtype=torch.int64, device=dev)
+        st.update(pos=pos, nz=nz)
+        kernels.append(Kernel(
+            "local_update_pack_ternary",
+            lambda: lc.lc_local_update_pack_ternary(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], 1, hp["beta2"],
+                                                    pos, nz, pos.stride(0)),
+            W * n * (4 + gb + 4 + 2 / 8)))
+        kernels.append(Kernel(
+            "vote_apply_ternary",
+            lambda: lc.lc_vote_apply_ternary(pos, nz, pos.stride(0), W, n, theta, hp["lr"], hp["wd"], None, 0, None, 0,
+                                             lc.LC_F32, 0, hp["beta2"]),
+            n * (2 * W / 8 + 8)))
     elif wl.mode == "l1":
         L = wl.levels
         q = torch.zeros((W, synth.round_up(n, 64)), dtype=torch.uint8, device=dev)
@@ -197,6 +211,9 @@ def cpu_baseline(wl, st, torch, sample, threads):
         def work(lo, hi):
             if wl.mode == "1bit":
                 r = orc.step_1bit(theta[lo:hi], m[:, lo:hi], g[:, lo:hi], g_dtype=gd, **kw)
+            elif wl.mode == "ternary":
+                kt = {k: v for k, v in kw.items() if k != "step"}
+                r = orc.step_ternary(theta[lo:hi], m[:, lo:hi], g[:, lo:hi], g_dtype=gd, **kt)
             elif wl.mode == "l1":   # per-chunk scales: same work per element as per-call scales
                 r = orc.step_l1(theta[lo:hi], m[:, lo:hi], g[:, lo:hi], L=wl.levels, g_dtype=gd, **kw)
             else:

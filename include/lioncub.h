@@ -128,6 +128,28 @@ int lc_pbit_sum_apply(const void *q, size_t q_stride_bytes, int in_bits, int W, 
                       size_t g_stride_elems, int g_dtype, int n_m, float beta2,
                       void *stream);
 
+/* ---- Ternary ("2-bit") wire format: exact zeros travel (Appendix B.1) ------------------
+ * The worker's sign s = sign(c) in {-1, 0, +1} is sent unchanged as two 1-bit planes per
+ * worker, pos (s > 0) and nz (s != 0), nothing is forced; the update is the sign of the
+ * plain sum of the signs, S = K+ - K-, and a zero sum is 0.  Rows of pos and of nz share
+ * one stride (in 64-bit words); 1-bit layout as above. */
+int lc_local_update_pack_ternary(const void *g, size_t g_stride_elems, int g_dtype, float *m,
+                                 size_t m_stride_elems, int W, size_t n, float beta1,
+                                 int update_m, float beta2, uint64_t *pos, uint64_t *nz,
+                                 size_t q_stride_words, void *stream);
+
+/* K+ = rows with pos set, K- = rows with nz set and pos clear; u = sign(K+ - K-) as the
+ * two planes vote_pos / vote_nz (either may be NULL).  A pos bit without its nz bit is
+ * ignored. */
+int lc_vote_ternary(const uint64_t *pos, const uint64_t *nz, size_t q_stride_words, int W,
+                    size_t n, uint64_t *vote_pos, uint64_t *vote_nz, void *stream);
+
+/* lc_vote_ternary followed by lc_apply_update without writing the planes. */
+int lc_vote_apply_ternary(const uint64_t *pos, const uint64_t *nz, size_t q_stride_words, int W,
+                          size_t n, float *theta, float lr, float wd, float *m,
+                          size_t m_stride_elems, const void *g, size_t g_stride_elems,
+                          int g_dtype, int n_m, float beta2, void *stream);
+
 /* ---- L1-quantised updates (Section 4.2, Equation 1 with p = 1; Appendix F.1) ---------
  * Q_1(x)_i = clamp(round(L / (2 M_1(x)) * x_i), L) with M_1(x) = mean_j |x_j| and
  * L = 2^(bits-1) - 1 levels on each side of zero (the paper's 8-bit allreduce among 8

@@ -332,3 +332,36 @@ def step_l1(theta, m, g, *, L, beta1, beta2, lr, wd, step, tie=TIE_ZERO, g_dtype
     m_new = np.stack([momentum(m[w], g[w], beta2, g_dtype) for w in range(W)])
     return dict(c=c, mean_abs=means, levels=levels, fields=fields, K=K, S=S, u=u, pos=pos, nz=nz,
                 theta=theta_new, m=m_new)
+
+
+# ---- ternary wire format (Appendix B.1) --------------------------------------------------
+_ternary_vote = _sig("orc_ternary_vote", _i, _vp, _i, _sz, _vp, _vp, _vp, _vp)
+
+
+def ternary_vote(s):
+    """s: (W, n) int8 signs in {-1, 0, +1}.  Returns Kp, Kn, S (int32) and u (int8)."""
+    s = _arr(s, np.int8)
+    W, n = s.shape
+    Kp, Kn, S = (np.empty(n, np.int32) for _ in range(3))
+    u = np.empty(n, np.int8)
+    rc = _ternary_vote(_p(s), W, n, _p(Kp), _p(Kn), _p(S), _p(u))
+    if rc:
+        raise OracleError(rc, "ternary_vote")
+    return Kp, Kn, S, u
+
+
+def step_ternary(theta, m, g, *, beta1, beta2, lr, wd, g_dtype=F32):
+    """One whole step with exact zeros on the wire: each worker's ternary sign travels as
+    two 1-bit planes (pos = s > 0, nz = s != 0); the update is sign(sum of signs)."""
+    m = _arr(m, np.float32)
+    W, n = m.shape
+    s = np.stack([local_sign(m[w], g[w], beta1, g_dtype) for w in range(W)])
+    pl = [planes(s[w]) for w in range(W)]
+    pos_w = np.stack([p[0] for p in pl])
+    nz_w = np.stack([p[1] for p in pl])
+    back = np.stack([unplanes(pos_w[w], nz_w[w], n) for w in range(W)])
+    Kp, Kn, S, u = ternary_vote(back)
+    pos, nz = planes(u)
+    theta_new = apply(theta, u, lr, wd)
+    m_new = np.stack([momentum(m[w], g[w], beta2, g_dtype) for w in range(W)])
+    return dict(s=s, pos_w=pos_w, nz_w=nz_w, Kp=Kp, Kn=Kn, S=S, u=u, pos=pos, nz=nz, theta=theta_new, m=m_new)

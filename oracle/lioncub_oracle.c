@@ -336,3 +336,27 @@ int orc_level_sum_sign(const uint8_t *rows, int W, size_t n, int L, uint64_t ste
     }
     return ORC_OK;
 }
+
+/* ==== Ternary ("2-bit") wire format (Appendix B.1: an allreduce that transmits exact
+ * zeros, the reference the alternating-sign rule is compared with) ==================
+ * Every worker sends its sign s in {-1, 0, +1} unchanged; the update is the sign of the
+ * plain sum of the signs (Algorithm 1 lines 4-5 with Q = sign and nothing forced).
+ * s: W rows of n signs.  Kp / Kn: how many workers voted +1 / -1; S = Kp - Kn. */
+int orc_ternary_vote(const int8_t *s, int W, size_t n, int32_t *Kp, int32_t *Kn, int32_t *S, int8_t *u)
+{
+    if (W < 1) return ORC_ERR_ARG;
+    for (size_t i = 0; i < n; ++i) {
+        int32_t kp = 0, kn = 0;
+        for (int w = 0; w < W; ++w) {
+            const int8_t v = s[(size_t)w * n + i];
+            if (v > 0) ++kp;
+            if (v < 0) ++kn;
+        }
+        const int32_t sum = kp - kn;
+        if (Kp) Kp[i] = kp;
+        if (Kn) Kn[i] = kn;
+        if (S) S[i] = sum;
+        if (u) u[i] = (int8_t)((sum > 0) - (sum < 0));
+    }
+    return ORC_OK;
+}

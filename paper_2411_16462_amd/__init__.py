@@ -34,6 +34,9 @@ SIGNATURES = {
     "lc_vote_apply_1bit": (_i, [_vp, _sz, _i, _sz, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
     "lc_pbit_sum_apply": (_i, [_vp, _sz, _i, _i, _sz, _i, _vp, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i,
                                _f, _vp]),
+    "lc_local_update_pack_ternary": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _i, _f, _vp, _vp, _sz, _vp]),
+    "lc_vote_ternary": (_i, [_vp, _vp, _sz, _i, _sz, _vp, _vp, _vp]),
+    "lc_vote_apply_ternary": (_i, [_vp, _vp, _sz, _i, _sz, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
     "lc_l1_mean_abs": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _vp, _vp, _vp]),
     "lc_l1_quantize_pack": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _i, _f, _i, _vp, _vp, _sz, _vp]),
     "lc_level_sum_sign": (_i, [_vp, _sz, _i, _sz, _i, _vp, _vp, _vp, _u64, _i, _vp]),
@@ -132,6 +135,23 @@ def lc_pbit_sum_apply(q, q_stride_bytes, in_bits, W, n, p, sum_out, step, tie_ru
     return _call("lc_pbit_sum_apply", check, _ptr(q), q_stride_bytes, in_bits, W, n, p, _ptr(sum_out), step,
                  tie_rule, _ptr(theta), lr, wd, _ptr(m), m_stride_elems, _ptr(g), g_stride_elems, g_dtype, n_m,
                  beta2, _stream(stream))
+
+
+def lc_local_update_pack_ternary(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, update_m, beta2, pos, nz,
+                                 q_stride_words, stream=None, check=True):
+    return _call("lc_local_update_pack_ternary", check, _ptr(g), g_stride_elems, g_dtype, _ptr(m), m_stride_elems, W, n,
+                 beta1, int(update_m), beta2, _ptr(pos), _ptr(nz), q_stride_words, _stream(stream))
+
+
+def lc_vote_ternary(pos, nz, q_stride_words, W, n, vote_pos, vote_nz, stream=None, check=True):
+    return _call("lc_vote_ternary", check, _ptr(pos), _ptr(nz), q_stride_words, W, n, _ptr(vote_pos), _ptr(vote_nz),
+                 _stream(stream))
+
+
+def lc_vote_apply_ternary(pos, nz, q_stride_words, W, n, theta, lr, wd, m, m_stride_elems, g, g_stride_elems, g_dtype,
+                          n_m, beta2, stream=None, check=True):
+    return _call("lc_vote_apply_ternary", check, _ptr(pos), _ptr(nz), q_stride_words, W, n, _ptr(theta), lr, wd,
+                 _ptr(m), m_stride_elems, _ptr(g), g_stride_elems, g_dtype, n_m, beta2, _stream(stream))
 
 
 def lc_l1_mean_abs(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, mean_abs, workspace, stream=None,

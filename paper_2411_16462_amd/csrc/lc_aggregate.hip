@@ -43,7 +43,7 @@ constexpr int kAggBlock = kAggWave * kWaves;  // elements per workgroup
 constexpr int kAggTiles = kAggWave / 256;
 constexpr int kPhases = kWave / kAggWords;    // lanes that share a word in phase A
 
-enum { IN_PLANES = 0, IN_BITS = 1 /* 2, 4, 8: field width */ };
+enum { IN_PLANES = 0, IN_BITS = 1 /* 2, 4, 8: field width */, IN_TERNARY = 16 /* pos + nz rows */ };
 
 // a + b + c = 2 h + l, bitwise in every position
 __device__ __forceinline__ void csa(uint64_t &h, uint64_t &l, uint64_t a, uint64_t b, uint64_t c)
@@ -62,6 +62,33 @@ __device__ __forceinline__ void ripple(uint64_t (&c)[8], uint64_t x, int from)
         const uint64_t t = c[k] & x;
         c[k] ^= x;
         x = t;
+    }
+}
+
+// eight more words into the planes: seven carry-save adders and one ripple from plane 3
+__device__ __forceinline__ void csa8(uint64_t (&c)[8], const uint64_t (&x)[8])
+{
+    uint64_t ta, tb, fa, fb, e;
+    csa(ta, c[0], c[0], x[0], x[1]);
+    csa(tb, c[0], c[0], x[2], x[3]);
+    csa(fa, c[1], c[1], ta, tb);
+    csa(ta, c[0], c[0], x[4], x[5]);
+    csa(tb, c[0], c[0], x[6], x[7]);
+    csa(fb, c[1], c[1], ta, tb);
+    csa(e, c[2], c[2], fa, fb);
+    ripple(c, e, 3);
+}
+
+// A > B and A == B for two bit-sliced counts, scanning from the top plane down.
+__device__ __forceinline__ void compare_two(const uint64_t (&a)[8], const uint64_t (&b)[8], uint64_t &gt, uint64_t &eq)
+{
+    gt = 0;
+    eq = ~0ull;
+#pragma unroll
+    for (int k = 7; k >= 0; --k) {
+        const uint64_t d = a[k] ^ b[k];
+        gt |= eq & d & a[k];
+        eq &= ~d;
     }
 }
 
@@ -243,15 +270,7 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
             uint64_t x[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) x[i] = vm ? ld_packed(qp + static_cast<size_t>(k + i) * step4) : 0ull;
-            uint64_t ta, tb, fa, fb, e;
-            csa(ta, c[0], c[0], x[0], x[1]);
-            csa(tb, c[0], c[0], x[2], x[3]);
-            csa(fa, c[1], c[1], ta, tb);
-            csa(ta, c[0], c[0], x[4], x[5]);
-            csa(tb, c[0], c[0], x[6], x[7]);
-            csa(fb, c[1], c[1], ta, tb);
-            csa(e, c[2], c[2], fa, fb);
-            ripple(c, e, 3);
+            csa8(c, x);
         }
         for (; k < most; ++k) {
             const bool have = vm && (ph + k * kPhases < W);
@@ -272,6 +291,57 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
                 for (int i = 0; i < 8; ++i) s_cnt[KOUT ? wave : 0][KOUT ? i : 0][KOUT ? j : 0] = c[i] & vm;
                 if (P.sum_bits == 1 && vm) static_cast<uint64_t *>(P.sum_out)[jw] = c[0] & vm;  // W = 1: K is the bit
             }
+            if (vm) {
+                if (P.vote_pos) P.vote_pos[jw] = pos;
+                if (P.vote_nz) P.vote_nz[jw] = nz;
+            }
+        }
+    } else if constexpr (IN == IN_TERNARY) {
+        // Every worker sends two planes, pos (s > 0) and nz (s != 0): count the +1 votes and
+        // the -1 votes separately, the update is the sign of their difference.
+        const int j = lane & (kAggWords - 1);
+        const int ph = lane / kAggWords;
+        const size_t jw = wave_base / 64 + j;
+        const uint64_t vm = valid_mask(jw * 64, n);
+        const size_t stride = P.q_stride_bytes / 8;
+        const uint64_t *pp = static_cast<const uint64_t *>(P.q) + jw + static_cast<size_t>(ph) * stride;
+        const uint64_t *zp = static_cast<const uint64_t *>(P.q2) + jw + static_cast<size_t>(ph) * stride;
+        const size_t step4 = stride * kPhases;
+        const int np = 32 - __builtin_clz(static_cast<unsigned>(W));
+        uint64_t cp[8] = {0, 0, 0, 0, 0, 0, 0, 0}, cn[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        const int every = W / kPhases;
+        const int most = (W + kPhases - 1) / kPhases;
+        int k = 0;
+        for (; k + 8 <= every; k += 8) {
+            uint64_t xp[8], xn[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint64_t a = vm ? ld_packed(pp + static_cast<size_t>(k + i) * step4) : 0ull;
+                const uint64_t z = vm ? ld_packed(zp + static_cast<size_t>(k + i) * step4) : 0ull;
+                xp[i] = a & z;
+                xn[i] = z & ~a;
+            }
+            csa8(cp, xp);
+            csa8(cn, xn);
+        }
+        for (; k < most; ++k) {
+            const bool have = vm && (ph + k * kPhases < W);
+            const uint64_t a = have ? ld_packed(pp + static_cast<size_t>(k) * step4) : 0ull;
+            const uint64_t z = have ? ld_packed(zp + static_cast<size_t>(k) * step4) : 0ull;
+            ripple(cp, a & z, 0);
+            ripple(cn, z & ~a, 0);
+        }
+#pragma unroll
+        for (int mask = kAggWords; mask < kWave; mask <<= 1) {
+            add_partner(cp, lane, mask, np);
+            add_partner(cn, lane, mask, np);
+        }
+        uint64_t gt, eq;
+        compare_two(cp, cn, gt, eq);
+        const uint64_t pos = gt & vm, nz = ~eq & vm;
+        if (ph == 0) {
+            s_pos[wave][j] = pos;
+            s_nz[wave][j] = nz;
             if (vm) {
                 if (P.vote_pos) P.vote_pos[jw] = pos;
                 if (P.vote_nz) P.vote_nz[jw] = nz;
@@ -350,7 +420,7 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
     }
     wave_lds_sync();
 
-    if (IN != IN_PLANES && IN != IN_BITS && lane < kAggWords) {
+    if (IN != IN_PLANES && IN != IN_BITS && IN != IN_TERNARY && lane < kAggWords) {
         // planes for the caller, from LDS in word order
         const size_t jw = wave_base / 64 + lane;
         if (jw * 64 < n) {
@@ -474,12 +544,13 @@ static hipError_t launch_in(const AggParams &P, bool apply, int g_dtype, hipStre
 }
 
 // Host launcher; arguments were validated by the caller.  in_kind: 0 planes, 1 bits,
-// 2/4/8 fields.  kout: counts wanted from 1-bit rows.
+// 2/4/8 fields, 16 ternary (pos + nz rows).  kout: counts wanted from 1-bit rows.
 hipError_t launch_aggregate(const AggParams &P, int in_kind, bool apply, bool kout, int g_dtype, hipStream_t s)
 {
     switch (in_kind) {
     case IN_PLANES: return launch_in<IN_PLANES, false>(P, apply, g_dtype, s);
     case IN_BITS: return kout ? launch_in<IN_BITS, true>(P, apply, g_dtype, s) : launch_in<IN_BITS, false>(P, apply, g_dtype, s);
+    case IN_TERNARY: return launch_in<IN_TERNARY, false>(P, apply, g_dtype, s);
     case 2: return launch_in<2, false>(P, apply, g_dtype, s);
     case 4: return launch_in<4, false>(P, apply, g_dtype, s);
     default: return launch_in<8, false>(P, apply, g_dtype, s);

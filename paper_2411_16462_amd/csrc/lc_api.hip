@@ -34,7 +34,7 @@ int tie_code(int tie_rule, uint64_t step)
 }
 
 // shared by the four aggregation entry points
-int aggregate(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n, int p, int levels, void *sum_out, uint64_t *vote_pos,
+int aggregate(const void *q, const void *q2, size_t q_stride_bytes, int in_bits, int W, size_t n, int p, int levels, void *sum_out, uint64_t *vote_pos,
               uint64_t *vote_nz, uint64_t step, int tie_rule, bool apply, float *theta, float lr, float wd, float *m,
               size_t m_stride, const void *g, size_t g_stride, int g_dtype, int n_m, float beta2, void *stream)
 {
@@ -49,11 +49,12 @@ int aggregate(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n
         if (sum_bits < 0) return LC_ERR_RANGE;
         if (W > (1 << p) - 1) return LC_ERR_RANGE;
         if (in_bits != 1 && in_bits != sum_bits) return LC_ERR_MODE;
-    } else if (in_bits != 1) {
+    } else if (in_bits != 1 && in_bits != 16) {
         return LC_ERR_MODE;
     }
-    if (!q) return LC_ERR_NULL;
-    if (in_bits == 1) {
+    if (!q || (in_bits == 16 && !q2)) return LC_ERR_NULL;
+    if (in_bits == 16 && !aligned(q2, 8)) return LC_ERR_ALIGN;
+    if (in_bits == 1 || in_bits == 16) {
         if (!aligned(q, 8) || (W > 1 && q_stride_bytes % 8 != 0)) return LC_ERR_ALIGN;
     } else {
         if (!aligned(q, 16) || (W > 1 && q_stride_bytes % 16 != 0)) return LC_ERR_ALIGN;
@@ -72,6 +73,7 @@ int aggregate(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n
     if (n == 0) return LC_OK;
     AggParams P{};
     P.q = q;
+    P.q2 = q2;
     P.q_stride_bytes = q_stride_bytes;
     P.W = W;
     P.n = n;
@@ -127,7 +129,7 @@ int lc_local_update_pack(const void *g, size_t g_stride_elems, int g_dtype, floa
 int lc_vote_1bit(const uint64_t *q, size_t q_stride_words, int W, size_t n, uint64_t *vote_pos, uint64_t *vote_nz,
                  uint64_t step, int tie_rule, void *stream)
 {
-    return aggregate(q, q_stride_words * 8, 1, W, n, 0, 0, nullptr, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f, 0.0f,
+    return aggregate(q, nullptr, q_stride_words * 8, 1, W, n, 0, 0, nullptr, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f, 0.0f,
                      nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream);
 }
 
@@ -135,7 +137,7 @@ int lc_pbit_sum_sign(const void *q, size_t q_stride_bytes, int in_bits, int W, s
                      uint64_t *vote_pos, uint64_t *vote_nz, uint64_t step, int tie_rule, void *stream)
 {
     if (p == 0) return LC_ERR_RANGE;
-    return aggregate(q, q_stride_bytes, in_bits, W, n, p, 0, sum_out, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f,
+    return aggregate(q, nullptr, q_stride_bytes, in_bits, W, n, p, 0, sum_out, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f,
                      0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream);
 }
 
@@ -143,7 +145,7 @@ int lc_vote_apply_1bit(const uint64_t *q, size_t q_stride_words, int W, size_t n
                        float lr, float wd, float *m, size_t m_stride_elems, const void *g, size_t g_stride_elems, int g_dtype,
                        int n_m, float beta2, void *stream)
 {
-    return aggregate(q, q_stride_words * 8, 1, W, n, 0, 0, nullptr, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
+    return aggregate(q, nullptr, q_stride_words * 8, 1, W, n, 0, 0, nullptr, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
                      m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
 }
 
@@ -152,7 +154,7 @@ int lc_pbit_sum_apply(const void *q, size_t q_stride_bytes, int in_bits, int W, 
                       size_t g_stride_elems, int g_dtype, int n_m, float beta2, void *stream)
 {
     if (p == 0) return LC_ERR_RANGE;
-    return aggregate(q, q_stride_bytes, in_bits, W, n, p, 0, sum_out, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
+    return aggregate(q, nullptr, q_stride_bytes, in_bits, W, n, p, 0, sum_out, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
                      m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
 }
 
@@ -229,7 +231,7 @@ int lc_level_sum_sign(const uint8_t *q, size_t q_stride_bytes, int W, size_t n, 
                       uint64_t *vote_pos, uint64_t *vote_nz, uint64_t step, int tie_rule, void *stream)
 {
     if (levels == 0) return LC_ERR_RANGE;
-    return aggregate(q, q_stride_bytes, 8, W, n, 0, levels, sum_out, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f,
+    return aggregate(q, nullptr, q_stride_bytes, 8, W, n, 0, levels, sum_out, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f,
                      0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream);
 }
 
@@ -238,8 +240,38 @@ int lc_level_sum_apply(const uint8_t *q, size_t q_stride_bytes, int W, size_t n,
                        size_t g_stride_elems, int g_dtype, int n_m, float beta2, void *stream)
 {
     if (levels == 0) return LC_ERR_RANGE;
-    return aggregate(q, q_stride_bytes, 8, W, n, 0, levels, sum_out, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
+    return aggregate(q, nullptr, q_stride_bytes, 8, W, n, 0, levels, sum_out, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
                      m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
+}
+
+int lc_local_update_pack_ternary(const void *g, size_t g_stride_elems, int g_dtype, float *m, size_t m_stride_elems, int W,
+                                 size_t n, float beta1, int update_m, float beta2, uint64_t *pos, uint64_t *nz,
+                                 size_t q_stride_words, void *stream)
+{
+    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
+    if (rc) return rc;
+    if (!pos || !nz) return LC_ERR_NULL;
+    if (!aligned(pos, 8) || !aligned(nz, 8)) return LC_ERR_ALIGN;
+    if (n == 0) return LC_OK;
+    return from_hip(launch_local_update_pack_ternary(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1,
+                                                     update_m != 0, beta2, pos, nz, q_stride_words,
+                                                     static_cast<hipStream_t>(stream)));
+}
+
+int lc_vote_ternary(const uint64_t *pos, const uint64_t *nz, size_t q_stride_words, int W, size_t n, uint64_t *vote_pos,
+                    uint64_t *vote_nz, void *stream)
+{
+    return aggregate(pos, nz, q_stride_words * 8, 16, W, n, 0, 0, nullptr, vote_pos, vote_nz, 1, LC_TIE_ZERO, false, nullptr,
+                     0.0f, 0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream);
+}
+
+int lc_vote_apply_ternary(const uint64_t *pos, const uint64_t *nz, size_t q_stride_words, int W, size_t n, float *theta,
+                          float lr, float wd, float *m, size_t m_stride_elems, const void *g, size_t g_stride_elems,
+                          int g_dtype, int n_m, float beta2, void *stream)
+{
+    return aggregate(pos, nz, q_stride_words * 8, 16, W, n, 0, 0, nullptr, nullptr, nullptr, 1, LC_TIE_ZERO, true, theta, lr,
+                     wd, m, m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
 }
 
 int lc_container_bits(int p) { return container(p); }

@@ -8,6 +8,7 @@ namespace lc {
 
 struct AggParams {
     const void *q;          // packed rows (1-bit words or fields); unused for IN_PLANES
+    const void *q2;         // ternary input: the nz rows (q holds the pos rows), same stride
     size_t q_stride_bytes;
     int W;
     size_t n;
@@ -33,10 +34,14 @@ struct AggParams {
 hipError_t launch_local_update_pack(const void *g, size_t g_stride, int g_dtype, float *m, size_t m_stride, int W, size_t n,
                                     float beta1, bool update_m, float beta2, int out_bits, void *q, size_t q_stride_bytes,
                                     int zero_bit, hipStream_t s);
-// in_kind: 0 = vote planes, 1 = 1-bit rows, 2 / 4 / 8 = field rows of that width.
+// in_kind: 0 = vote planes, 1 = 1-bit rows, 2 / 4 / 8 = field rows of that width,
+// 16 = ternary rows (pos in q, nz in q2).
 // kout: the counts K are wanted as fields from 1-bit rows.
 hipError_t launch_aggregate(const AggParams &P, int in_kind, bool apply, bool kout, int g_dtype, hipStream_t s);
 hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStream_t s);
+hipError_t launch_local_update_pack_ternary(const void *g, size_t g_stride, int g_dtype, float *m, size_t m_stride, int W,
+                                            size_t n, float beta1, bool update_m, float beta2, uint64_t *pos, uint64_t *nz,
+                                            size_t stride_words, hipStream_t s);
 
 // L1 quantisation (Equation 1, p = 1)
 constexpr int kL1Limbs = 12;  // 64-bit accumulators, 32 bits apart

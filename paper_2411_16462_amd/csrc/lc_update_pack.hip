@@ -151,6 +151,87 @@ __global__ __launch_bounds__(kPackThreads) void local_update_pack_kernel(
     }
 }
 
+// Ternary wire format (Appendix B.1's allreduce that transmits exact zeros): the sign
+// s = sign(c) in {-1, 0, +1} leaves the worker as two 1-bit planes, pos (s > 0) and nz
+// (s != 0); nothing is forced.  Same tiling and packing as the 1-bit kernel.
+template <int GDT, bool UPDATE_M>
+__global__ __launch_bounds__(kPackThreads) void local_update_pack_ternary_kernel(
+    const void *__restrict__ g, size_t g_stride, float *__restrict__ m, size_t m_stride, size_t n, float beta1, float omb1,
+    float beta2, float omb2, uint64_t *__restrict__ pos, uint64_t *__restrict__ nz, size_t stride_words)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const size_t w = blockIdx.y;
+    const size_t wave_base = static_cast<size_t>(blockIdx.x) * kPackBlock + static_cast<size_t>(wave) * kPackWave;
+    if (wave_base >= n) return;
+    float *mrow = m + w * m_stride;
+    const void *grow = static_cast<const char *>(g) + w * g_stride * Grad<GDT>::kBytes;
+    uint64_t *prow = pos + w * stride_words;
+    uint64_t *zrow = nz + w * stride_words;
+
+    if (wave_base + kPackWave <= n) {
+#pragma unroll
+        for (int t = 0; t < kPackTiles; ++t) {
+            const size_t e = wave_base + t * 256 + lane * 4;
+            f32x4 mv = load4(mrow + e);
+            const f32x4 gv = Grad<GDT>::load4(grow, e);
+            uint32_t pb = 0, zb = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float c = interpolate(mv[k], gv[k], beta1, omb1);
+                pb |= static_cast<uint32_t>(c > 0.0f) << k;
+                zb |= static_cast<uint32_t>(c > 0.0f || c < 0.0f) << k;
+                if (UPDATE_M) mv[k] = momentum_step(mv[k], gv[k], beta2, omb2);
+            }
+            if (UPDATE_M) store4(mrow + e, mv);
+            const uint32_t pd = or_reduce8(pb << (4 * (lane & 7)));
+            const uint32_t zd = or_reduce8(zb << (4 * (lane & 7)));
+            const size_t d = (wave_base + t * 256) / 32 + (lane >> 3);  // dword of this group of 8 lanes
+            if ((lane & 7) == 0) reinterpret_cast<uint32_t *>(prow)[d] = pd;
+            if ((lane & 7) == 1) reinterpret_cast<uint32_t *>(zrow)[d] = zd;
+        }
+        return;
+    }
+    const size_t wave_end = (wave_base + kPackWave < n) ? wave_base + kPackWave : n;
+    for (size_t b = wave_base; b < wave_end; b += kWave) {
+        const size_t i = b + lane;
+        bool p = false, z = false;
+        if (i < n) {
+            const float mm = ld_stream(mrow + i);
+            const float gg = Grad<GDT>::load1(grow, i);
+            const float c = interpolate(mm, gg, beta1, omb1);
+            p = c > 0.0f;
+            z = c > 0.0f || c < 0.0f;
+            if (UPDATE_M) st_stream(mrow + i, momentum_step(mm, gg, beta2, omb2));
+        }
+        const uint64_t pm = __ballot(p), zm = __ballot(z);
+        if (lane == 0) {
+            prow[b / 64] = pm;
+            zrow[b / 64] = zm;
+        }
+    }
+}
+
+hipError_t launch_local_update_pack_ternary(const void *g, size_t g_stride, int g_dtype, float *m, size_t m_stride, int W,
+                                            size_t n, float beta1, bool update_m, float beta2, uint64_t *pos, uint64_t *nz,
+                                            size_t stride_words, hipStream_t s)
+{
+    const dim3 grid(static_cast<unsigned>((n + kPackBlock - 1) / kPackBlock), static_cast<unsigned>(W));
+    const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+#define LC_LAUNCH(GDT, UPD)                                                                                              \
+    local_update_pack_ternary_kernel<GDT, UPD><<<grid, kPackThreads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, \
+                                                                             beta2, omb2, pos, nz, stride_words)
+    if (g_dtype == LC_BF16) {
+        if (update_m) LC_LAUNCH(LC_BF16, true);
+        else LC_LAUNCH(LC_BF16, false);
+    } else {
+        if (update_m) LC_LAUNCH(LC_F32, true);
+        else LC_LAUNCH(LC_F32, false);
+    }
+#undef LC_LAUNCH
+    return hipGetLastError();
+}
+
 template <int GDT, int OUT_BITS>
 static hipError_t launch_pack(bool update_m, dim3 grid, hipStream_t s, const void *g, size_t g_stride, float *m,
                               size_t m_stride, size_t n, float beta1, float omb1, float beta2, float omb2, void *q,

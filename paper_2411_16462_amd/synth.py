@@ -48,7 +48,7 @@ class Workload:
     name: str
     n: int                      # parameters in the flat arena
     W: int                      # simulated workers
-    mode: str                   # "1bit" | "pbit" | "prepacked" | "l1"
+    mode: str                   # "1bit" | "pbit" | "prepacked" | "l1" | "ternary"
     p: int = 1                  # bits per summed field (pbit / prepacked-sum)
     levels: int = 0             # l1: levels on each side of zero (L = 15: Appendix F.1's 8-bit case)
     dist: str = "normal"        # gradient noise: "normal" | "laplace" (Section 4.1: updates look Laplacian)
@@ -81,6 +81,8 @@ def workloads() -> List[Workload]:
                  seed=0x11C4),
         # beyond the five benchmark configurations: the paper's 8-bit L1-quantised allreduce
         # among 8 workers (Appendix F.1), levels in [-15, 15], on the GPT-2-small shapes
+        # ... and the ternary ("2-bit") wire format of Appendix B.1 on the same shapes
+        Workload("t2_gpt2s_w8_ternary", n_small, 8, "ternary", tensors=small, seed=0x11C6),
         Workload("l1_gpt2s_w8_l15", n_small, 8, "l1", levels=15, dist="laplace", tensors=small,
                  seed=0x11C5),
     ]

@@ -170,3 +170,21 @@ def test_l1_validation():
     assert lc.lc_level_sum_apply(**ap) == lc.LC_OK
     assert lc.lc_level_sum_apply(**{**ap, "theta": None}) == lc.LC_ERR_NULL
     assert lc.lc_level_sum_apply(**{**ap, "W": 9}) == lc.LC_ERR_RANGE
+
+
+def test_ternary_validation():
+    pk = dict(g=A, g_stride_elems=1024, g_dtype=lc.LC_F32, m=A, m_stride_elems=1024, W=4, n=0, beta1=0.9, update_m=1,
+              beta2=0.99, pos=A, nz=A, q_stride_words=16, stream=0, check=False)
+    assert lc.lc_local_update_pack_ternary(**pk) == lc.LC_OK
+    assert lc.lc_local_update_pack_ternary(**{**pk, "nz": None}) == lc.LC_ERR_NULL
+    assert lc.lc_local_update_pack_ternary(**{**pk, "pos": A + 4}) == lc.LC_ERR_ALIGN
+    assert lc.lc_local_update_pack_ternary(**{**pk, "W": 256}) == lc.LC_ERR_SIZE
+    vt = dict(pos=A, nz=A, q_stride_words=16, W=4, n=0, vote_pos=A, vote_nz=None, stream=0, check=False)
+    assert lc.lc_vote_ternary(**vt) == lc.LC_OK
+    assert lc.lc_vote_ternary(**{**vt, "nz": None}) == lc.LC_ERR_NULL
+    assert lc.lc_vote_ternary(**{**vt, "nz": A + 4}) == lc.LC_ERR_ALIGN
+    va = dict(pos=A, nz=A, q_stride_words=16, W=4, n=0, theta=A, lr=1e-4, wd=0.1, m=None, m_stride_elems=0, g=None,
+              g_stride_elems=0, g_dtype=lc.LC_F32, n_m=0, beta2=0.99, stream=0, check=False)
+    assert lc.lc_vote_apply_ternary(**va) == lc.LC_OK
+    assert lc.lc_vote_apply_ternary(**{**va, "theta": None}) == lc.LC_ERR_NULL
+    assert lc.lc_vote_apply_ternary(**{**va, "n_m": 1}) == lc.LC_ERR_NULL

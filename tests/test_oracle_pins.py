@@ -493,3 +493,36 @@ def test_whole_step_brute_force_rationals(W, n, step):
         assert sum(int(x) << (64 * j) for j, x in enumerate(r["words"][w].tolist())) == big[w]
     assert (r["s"][:, : n // 4] == 0).all()
     assert np.array_equal(r["theta"], rp["theta"]) and np.array_equal(r["pos"], rp["pos"])
+
+
+# --------------------------------------------------------------------------------------
+# ternary wire format (Appendix B.1): exact zeros travel, the vote is the sign of the sum
+# --------------------------------------------------------------------------------------
+@pytest.mark.parametrize("W", range(1, 8))
+def test_ternary_vote_brute_force(W):
+    cols = np.array(list(itertools.product([-1, 0, 1], repeat=W)), np.int8).T.copy()     # all 3^W columns
+    Kp, Kn, S, u = orc.ternary_vote(cols)
+    for j in range(cols.shape[1]):
+        col = [int(x) for x in cols[:, j]]
+        tot = sum(col)
+        assert (Kp[j], Kn[j], S[j], u[j]) == (col.count(1), col.count(-1), tot, (tot > 0) - (tot < 0))
+    assert (Kp + Kn <= W).all()
+
+
+def test_ternary_hand_case_and_difference_to_one_bit(hand):
+    """The hand case's last element has gradient 0 on every worker: the 1-bit path votes
+    it +1 or -1 by iteration parity, the ternary format keeps it 0 (what Appendix B.1's
+    2-bit allreduce transmits).  Elsewhere, without zeros, both agree."""
+    gold, g = hand
+    theta = np.zeros(8, np.float32)
+    m = np.zeros((3, 8), np.float32)
+    r = orc.step_ternary(theta, m, g[:3], beta1=0.9, beta2=0.99, lr=1e-4, wd=0.0)
+    assert r["S"].tolist() == _ints(gold["step1.W3.S"])[:7] + [0]
+    assert r["u"].tolist() == [1, -1, -1, -1, 1, -1, 1, 0]
+    assert [int(r["pos"][0]), int(r["nz"][0])] == [0x51, 0x7F]
+    assert [int(x) for x in r["pos_w"][:, 0]] == [0x53, 0x19, 0x45]          # = the even-iteration 1-bit words
+    assert [int(x) for x in r["nz_w"][:, 0]] == [0x7F, 0x7F, 0x7F]
+    one = orc.step_1bit(theta, m, g[:3], beta1=0.9, beta2=0.99, lr=1e-4, wd=0.0, step=1)
+    assert one["u"][:7].tolist() == r["u"][:7].tolist() and one["u"][7] == 1 and r["u"][7] == 0
+    r4 = orc.step_ternary(theta, np.zeros((4, 8), np.float32), g, beta1=0.9, beta2=0.99, lr=1e-4, wd=0.0)
+    assert r4["S"].tolist() == _ints(gold["step1.W4.S"])[:7] + [0]           # ties stay 0 by themselves
