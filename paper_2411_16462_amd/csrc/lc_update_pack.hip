@@ -170,22 +170,34 @@ __global__ __launch_bounds__(kPackThreads) void local_update_pack_ternary_kernel
     uint64_t *zrow = nz + w * stride_words;
 
     if (wave_base + kPackWave <= n) {
+        f32x4 mv[kPackTiles], gv[kPackTiles];
 #pragma unroll
         for (int t = 0; t < kPackTiles; ++t) {
             const size_t e = wave_base + t * 256 + lane * 4;
-            f32x4 mv = load4(mrow + e);
-            const f32x4 gv = Grad<GDT>::load4(grow, e);
-            uint32_t pb = 0, zb = 0;
+            mv[t] = load4(mrow + e);
+            gv[t] = Grad<GDT>::load4(grow, e);
+        }
+        uint32_t pb[kPackTiles], zb[kPackTiles];
+#pragma unroll
+        for (int t = 0; t < kPackTiles; ++t) {
+            pb[t] = 0;
+            zb[t] = 0;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const float c = interpolate(mv[k], gv[k], beta1, omb1);
-                pb |= static_cast<uint32_t>(c > 0.0f) << k;
-                zb |= static_cast<uint32_t>(c > 0.0f || c < 0.0f) << k;
-                if (UPDATE_M) mv[k] = momentum_step(mv[k], gv[k], beta2, omb2);
+                const float c = interpolate(mv[t][k], gv[t][k], beta1, omb1);
+                pb[t] |= static_cast<uint32_t>(c > 0.0f) << k;
+                zb[t] |= static_cast<uint32_t>(c > 0.0f || c < 0.0f) << k;
+                if (UPDATE_M) mv[t][k] = momentum_step(mv[t][k], gv[t][k], beta2, omb2);
             }
-            if (UPDATE_M) store4(mrow + e, mv);
-            const uint32_t pd = or_reduce8(pb << (4 * (lane & 7)));
-            const uint32_t zd = or_reduce8(zb << (4 * (lane & 7)));
+        }
+        if (UPDATE_M) {
+#pragma unroll
+            for (int t = 0; t < kPackTiles; ++t) store4(mrow + wave_base + t * 256 + lane * 4, mv[t]);
+        }
+#pragma unroll
+        for (int t = 0; t < kPackTiles; ++t) {
+            const uint32_t pd = or_reduce8(pb[t] << (4 * (lane & 7)));
+            const uint32_t zd = or_reduce8(zb[t] << (4 * (lane & 7)));
             const size_t d = (wave_base + t * 256) / 32 + (lane >> 3);  // dword of this group of 8 lanes
             if ((lane & 7) == 0) reinterpret_cast<uint32_t *>(prow)[d] = pd;
             if ((lane & 7) == 1) reinterpret_cast<uint32_t *>(zrow)[d] = zd;

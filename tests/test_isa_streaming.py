@@ -1,0 +1,59 @@
+"""Compile-time check (no GPU): the streaming kernels keep their non-temporal loads and
+stores.  The compiler has been seen to drop the hint when a kernel's code took a certain
+shape, which costs a quarter of the bandwidth without changing any result -- so the
+generated gfx950 assembly is checked here."""
+import os
+import re
+import subprocess
+
+import pytest
+
+from conftest import ROOT
+from paper_2411_16462_amd import build as hip_build
+
+CSRC = os.path.join(ROOT, "paper_2411_16462_amd", "csrc")
+
+
+def device_asm(name, tmp_path):
+    out = os.path.join(str(tmp_path), name + ".s")
+    flags = [f for f in hip_build.FLAGS if f not in ("-fPIC", "-Wall", "-Wextra")]
+    subprocess.check_call([hip_build.HIPCC, *flags, "-S", "--cuda-device-only", os.path.join(CSRC, name + ".hip"), "-o", out],
+                          stderr=subprocess.DEVNULL)
+    kernels, cur = {}, None
+    for line in open(out):
+        m = re.match(r"^(_ZN2lc\w+):", line)
+        if m:
+            cur = m.group(1)
+            kernels[cur] = []
+        elif cur and re.search(r"\bglobal_(load|store)_dwordx[24]\b", line):
+            kernels[cur].append(line.strip())
+        if line.startswith(".Lfunc_end"):
+            cur = None
+    return kernels
+
+
+@pytest.mark.parametrize("source,pattern", [
+    ("lc_update_pack", r"local_update_pack(_ternary)?_kernel"),
+    ("lc_momentum_avg", r"momentum_avg_kernel"),
+    ("lc_l1", r"l1_(abs_sum|quantize_pack)_kernel"),
+])
+def test_wide_accesses_are_non_temporal(source, pattern, tmp_path):
+    kernels = {k: v for k, v in device_asm(source, tmp_path).items() if re.search(pattern, k)}
+    assert kernels, "no kernel matched"
+    for name, lines in kernels.items():
+        wide = [l for l in lines if "dwordx4" in l]
+        assert wide, name
+        plain = [l for l in wide if not l.endswith(" nt")]
+        assert not plain, "%s: %d of %d 16-byte accesses lost the non-temporal hint: %s" % (name, len(plain), len(wide), plain[:2])
+
+
+def test_aggregate_theta_and_momentum_streams_are_non_temporal(tmp_path):
+    kernels = device_asm("lc_aggregate", tmp_path)
+    apply_kernels = {k: v for k, v in kernels.items() if re.search(r"aggregate_kernelILi\d+ELi\dELb1", k)}
+    assert len(apply_kernels) >= 12
+    for name, lines in apply_kernels.items():
+        stores = [l for l in lines if "store_dwordx4" in l]
+        assert stores and all(l.endswith(" nt") for l in stores), name
+        fields8 = re.search(r"aggregate_kernelILi8E", name)        # byte fields: 16-byte plain loads of packed rows
+        loads = [l for l in lines if "load_dwordx4" in l and l.endswith(" nt")]
+        assert len(loads) >= 4 or fields8, name                     # the four theta tiles (plus m, g streams)
