@@ -113,6 +113,21 @@ int lc_apply_update(float *theta, const uint64_t *vote_pos, const uint64_t *vote
  * total is multiplied once by 1/W; every row receives the same bits. */
 int lc_momentum_avg(float *m, size_t m_stride_elems, int W, size_t n, void *stream);
 
+/* Section 5.1, the quantity plotted per layer in Figure 6: the largest, over the n elements,
+ * standard deviation of an element's W momentum values across workers (divisor W).
+ * Evaluated in fp64, workers in order; *max_std (one double on the device) is written. */
+int lc_momentum_divergence(const float *m, size_t m_stride_elems, int W, size_t n,
+                           double *max_std, void *stream);
+
+/* Section 5 / 6.2, the policy the paper recommends: synchronise the momenta of selected
+ * layers only, every `every` iterations (e.g. head and embedding, every 10).  If step is a
+ * multiple of `every`, runs lc_momentum_avg on each range [offsets[r], offsets[r] +
+ * sizes[r]) of the rows; otherwise does nothing.  offsets and sizes are HOST arrays of
+ * n_ranges entries (element units; offsets multiples of 4); every >= 1. */
+int lc_momentum_sync_ranges(float *m, size_t m_stride_elems, int W, const size_t *offsets,
+                            const size_t *sizes, int n_ranges, uint64_t step, uint64_t every,
+                            void *stream);
+
 /* Fused forms: lc_vote_1bit followed by lc_apply_update without writing the planes. */
 int lc_vote_apply_1bit(const uint64_t *q, size_t q_stride_words, int W, size_t n,
                        uint64_t step, int tie_rule, float *theta, float lr, float wd,

@@ -365,3 +365,14 @@ def step_ternary(theta, m, g, *, beta1, beta2, lr, wd, g_dtype=F32):
     theta_new = apply(theta, u, lr, wd)
     m_new = np.stack([momentum(m[w], g[w], beta2, g_dtype) for w in range(W)])
     return dict(s=s, pos_w=pos_w, nz_w=nz_w, Kp=Kp, Kn=Kn, S=S, u=u, pos=pos, nz=nz, theta=theta_new, m=m_new)
+
+
+# ---- divergence of the workers' momenta (Section 5.1) ------------------------------------
+_momentum_divergence = _sig("orc_momentum_divergence", C.c_double, _vp, _i, _sz)
+
+
+def momentum_divergence(m):
+    """m: (W, n) float32.  max over elements of the standard deviation across workers."""
+    m = _arr(m, np.float32)
+    W, n = m.shape
+    return float(_momentum_divergence(_p(m), W, n))

@@ -360,3 +360,25 @@ int orc_ternary_vote(const int8_t *s, int W, size_t n, int32_t *Kp, int32_t *Kn,
     }
     return ORC_OK;
 }
+
+/* ==== Divergence of the workers' momenta (Section 5.1, the quantity of Figure 6) =====
+ * For every element the standard deviation of its W momentum values across workers
+ * (population form, divisor W -- the paper does not say which), and the maximum of that
+ * over the n elements of a layer.  Two-pass, fp64, workers in order. */
+double orc_momentum_divergence(const float *m, int W, size_t n)
+{
+    double worst = 0.0;
+    for (size_t i = 0; i < n; ++i) {
+        double sum = 0.0;
+        for (int w = 0; w < W; ++w) sum += (double)m[(size_t)w * n + i];
+        const double mean = sum / (double)W;
+        double ss = 0.0;
+        for (int w = 0; w < W; ++w) {
+            const double d = (double)m[(size_t)w * n + i] - mean;
+            ss += d * d;
+        }
+        const double sd = sqrt(ss / (double)W);
+        if (sd > worst) worst = sd;
+    }
+    return worst;
+}

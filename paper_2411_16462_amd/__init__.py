@@ -31,6 +31,8 @@ SIGNATURES = {
     "lc_pbit_sum_sign": (_i, [_vp, _sz, _i, _i, _sz, _i, _vp, _vp, _vp, _u64, _i, _vp]),
     "lc_apply_update": (_i, [_vp, _vp, _vp, _sz, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
     "lc_momentum_avg": (_i, [_vp, _sz, _i, _sz, _vp]),
+    "lc_momentum_divergence": (_i, [_vp, _sz, _i, _sz, _vp, _vp]),
+    "lc_momentum_sync_ranges": (_i, [_vp, _sz, _i, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), _i, _u64, _u64, _vp]),
     "lc_vote_apply_1bit": (_i, [_vp, _sz, _i, _sz, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
     "lc_pbit_sum_apply": (_i, [_vp, _sz, _i, _i, _sz, _i, _vp, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i,
                                _f, _vp]),
@@ -122,6 +124,18 @@ def lc_apply_update(theta, vote_pos, vote_nz, n, lr, wd, m, m_stride_elems, g, g
 
 def lc_momentum_avg(m, m_stride_elems, W, n, stream=None, check=True):
     return _call("lc_momentum_avg", check, _ptr(m), m_stride_elems, W, n, _stream(stream))
+
+
+def lc_momentum_divergence(m, m_stride_elems, W, n, max_std, stream=None, check=True):
+    return _call("lc_momentum_divergence", check, _ptr(m), m_stride_elems, W, n, _ptr(max_std), _stream(stream))
+
+
+def lc_momentum_sync_ranges(m, m_stride_elems, W, offsets, sizes, n_ranges, step, every, stream=None, check=True):
+    """offsets / sizes: sequences of ints (host side), marshalled to size_t arrays."""
+    off = (C.c_size_t * max(1, n_ranges))(*list(offsets)[:n_ranges]) if offsets is not None else None
+    siz = (C.c_size_t * max(1, n_ranges))(*list(sizes)[:n_ranges]) if sizes is not None else None
+    return _call("lc_momentum_sync_ranges", check, _ptr(m), m_stride_elems, W, off, siz, n_ranges, step, every,
+                 _stream(stream))
 
 
 def lc_vote_apply_1bit(q, q_stride_words, W, n, step, tie_rule, theta, lr, wd, m, m_stride_elems, g,

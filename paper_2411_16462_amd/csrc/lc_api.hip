@@ -274,6 +274,32 @@ int lc_vote_apply_ternary(const uint64_t *pos, const uint64_t *nz, size_t q_stri
                      wd, m, m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
 }
 
+int lc_momentum_divergence(const float *m, size_t m_stride_elems, int W, size_t n, double *max_std, void *stream)
+{
+    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    if (!m || !max_std) return LC_ERR_NULL;
+    if (!aligned(m, 16) || (W > 1 && (m_stride_elems * 4) % 16 != 0) || !aligned(max_std, 8)) return LC_ERR_ALIGN;
+    return from_hip(launch_momentum_divergence(m, m_stride_elems, W, n, max_std, static_cast<hipStream_t>(stream)));
+}
+
+int lc_momentum_sync_ranges(float *m, size_t m_stride_elems, int W, const size_t *offsets, const size_t *sizes, int n_ranges,
+                            uint64_t step, uint64_t every, void *stream)
+{
+    if (W < 1 || W > LC_MAX_W || n_ranges < 0) return LC_ERR_SIZE;
+    if (every == 0) return LC_ERR_MODE;
+    if (!m || (n_ranges > 0 && (!offsets || !sizes))) return LC_ERR_NULL;
+    if (!aligned(m, 16) || (W > 1 && (m_stride_elems * 4) % 16 != 0)) return LC_ERR_ALIGN;
+    for (int r = 0; r < n_ranges; ++r)
+        if (offsets[r] % 4 != 0) return LC_ERR_ALIGN;
+    if (step % every != 0 || W == 1) return LC_OK;  // not a synchronisation step
+    for (int r = 0; r < n_ranges; ++r) {
+        if (sizes[r] == 0) continue;
+        const hipError_t e = launch_momentum_avg(m + offsets[r], m_stride_elems, W, sizes[r], static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return from_hip(e);
+    }
+    return LC_OK;
+}
+
 int lc_container_bits(int p) { return container(p); }
 
 const char *lc_status_string(int status)

@@ -76,4 +76,72 @@ hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStre
     return hipGetLastError();
 }
 
+// ---- divergence of the workers' momenta (Section 5.1, the quantity of Figure 6) --------
+// max over elements of the standard deviation across the W workers (divisor W), in fp64
+// with the workers taken in order, so that the result equals a sequential evaluation bit
+// for bit; the maximum is order-free.  Reads W * 4 bytes per element, writes one double.
+__global__ void divergence_zero_kernel(double *out) { *out = 0.0; }
+
+__global__ __launch_bounds__(256) void momentum_divergence_kernel(const float *__restrict__ m, size_t stride, int W, size_t n,
+                                                                  double *__restrict__ out)
+{
+    __shared__ double s_max[4];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const size_t e = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
+    double worst = 0.0;  // largest sum of squared deviations of this lane's elements
+    if (e < n) {
+        double sum[4] = {0.0, 0.0, 0.0, 0.0};
+        for (int w = 0; w < W; ++w) {
+            const f32x4 v = load4_guarded(m + static_cast<size_t>(w) * stride, e, n);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) sum[k] += static_cast<double>(v[k]);
+        }
+        double mean[4], ss[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) mean[k] = sum[k] / static_cast<double>(W);
+        for (int w = 0; w < W; ++w) {  // second pass: the rows are still in cache
+            const f32x4 v = load4_guarded(m + static_cast<size_t>(w) * stride, e, n);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const double d = static_cast<double>(v[k]) - mean[k];
+                ss[k] += d * d;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (e + k < n && ss[k] > worst) worst = ss[k];
+    }
+    // non-negative doubles order like their bit patterns
+    unsigned long long bits = static_cast<unsigned long long>(__double_as_longlong(worst));
+#pragma unroll
+    for (int mask = 1; mask < kWave; mask <<= 1) {
+        const int addr = (lane ^ mask) << 2;
+        const unsigned lo = static_cast<unsigned>(__builtin_amdgcn_ds_bpermute(addr, static_cast<int>(bits & 0xFFFFFFFFull)));
+        const unsigned hi = static_cast<unsigned>(__builtin_amdgcn_ds_bpermute(addr, static_cast<int>(bits >> 32)));
+        const unsigned long long o = (static_cast<unsigned long long>(hi) << 32) | lo;
+        bits = o > bits ? o : bits;
+    }
+    if (lane == 0) s_max[wave] = __longlong_as_double(static_cast<long long>(bits));
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double b = s_max[0];
+        for (int r = 1; r < 4; ++r) b = s_max[r] > b ? s_max[r] : b;
+        if (b > 0.0) {
+            const double sd = sqrt(b / static_cast<double>(W));
+            atomicMax(reinterpret_cast<unsigned long long *>(out), static_cast<unsigned long long>(__double_as_longlong(sd)));
+        }
+    }
+}
+
+hipError_t launch_momentum_divergence(const float *m, size_t stride, int W, size_t n, double *out, hipStream_t s)
+{
+    divergence_zero_kernel<<<1, 1, 0, s>>>(out);
+    if (n > 0) {
+        const unsigned grid = static_cast<unsigned>((n + 1023) / 1024);
+        momentum_divergence_kernel<<<grid, 256, 0, s>>>(m, stride, W, n, out);
+    }
+    return hipGetLastError();
+}
+
 }  // namespace lc

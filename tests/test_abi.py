@@ -188,3 +188,20 @@ def test_ternary_validation():
     assert lc.lc_vote_apply_ternary(**va) == lc.LC_OK
     assert lc.lc_vote_apply_ternary(**{**va, "theta": None}) == lc.LC_ERR_NULL
     assert lc.lc_vote_apply_ternary(**{**va, "n_m": 1}) == lc.LC_ERR_NULL
+
+
+def test_divergence_and_sync_ranges_validation():
+    d = dict(m=A, m_stride_elems=1024, W=4, n=0, max_std=A, stream=0, check=False)
+    assert lc.lc_momentum_divergence(**{**d, "m": None}) == lc.LC_ERR_NULL
+    assert lc.lc_momentum_divergence(**{**d, "max_std": None}) == lc.LC_ERR_NULL
+    assert lc.lc_momentum_divergence(**{**d, "max_std": A + 4}) == lc.LC_ERR_ALIGN
+    assert lc.lc_momentum_divergence(**{**d, "W": 0}) == lc.LC_ERR_SIZE
+    s = dict(m=A, m_stride_elems=1024, W=4, offsets=[0, 64], sizes=[64, 128], n_ranges=2, step=3, every=10, stream=0,
+             check=False)
+    assert lc.lc_momentum_sync_ranges(**s) == lc.LC_OK                      # step 3 of every 10: nothing to do
+    assert lc.lc_momentum_sync_ranges(**{**s, "every": 0}) == lc.LC_ERR_MODE
+    assert lc.lc_momentum_sync_ranges(**{**s, "offsets": [0, 66]}) == lc.LC_ERR_ALIGN
+    assert lc.lc_momentum_sync_ranges(**{**s, "offsets": None}) == lc.LC_ERR_NULL
+    assert lc.lc_momentum_sync_ranges(**{**s, "m": None}) == lc.LC_ERR_NULL
+    assert lc.lc_momentum_sync_ranges(**{**s, "n_ranges": 0, "step": 10}) == lc.LC_OK
+    assert lc.lc_momentum_sync_ranges(**{**s, "sizes": [0, 0], "step": 10}) == lc.LC_OK   # empty ranges: no launch

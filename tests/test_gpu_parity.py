@@ -337,3 +337,44 @@ def test_errors_leave_buffers_untouched():
     torch.cuda.synchronize()
     assert (q == SENTINEL).all().item()
     assert np.array_equal(case.m.cpu().numpy(), case.m0) and np.array_equal(case.theta.cpu().numpy(), case.theta0)
+
+
+@pytest.mark.parametrize("W", [2, 3, 8, 16])
+@pytest.mark.parametrize("n", [1, 5, 1023, 1024, 1025, 200003])
+def test_momentum_divergence(W, n):
+    """Section 5.1's metric: max over elements of the std across workers, fp64."""
+    case = Case(n, W, seed=14000 + W + n, m_spread=0.3)
+    out = torch.full((1,), -1.0, dtype=torch.float64, device="cuda")
+    lc.lc_momentum_divergence(case.m, case.m.stride(0), W, n, out)
+    torch.cuda.synchronize()
+    ref = orc.momentum_divergence(case.m0)
+    assert ref > 0 and abs(float(out[0]) - ref) <= 1e-12 * ref
+    lc.lc_momentum_avg(case.m, case.m.stride(0), W, n)
+    lc.lc_momentum_divergence(case.m, case.m.stride(0), W, n, out)
+    torch.cuda.synchronize()
+    assert float(out[0]) == 0.0                                              # synchronised: no divergence left
+    lc.lc_momentum_divergence(case.m, case.m.stride(0), W, 0, out)
+    torch.cuda.synchronize()
+    assert float(out[0]) == 0.0
+
+
+def test_momentum_sync_ranges_policy():
+    """Selected ranges only, and only on every k-th iteration (Section 6.2: head and
+    embedding every ten iterations)."""
+    n, W = 64 * 300, 4
+    case = Case(n, W, seed=15000, m_spread=1.0)
+    offsets, sizes = [0, 64 * 100, 64 * 250], [64 * 10, 64 * 7 + 12, 64 * 50]
+    for step in (1, 7, 9):
+        lc.lc_momentum_sync_ranges(case.m, case.m.stride(0), W, offsets, sizes, 3, step, 10)
+    torch.cuda.synchronize()
+    assert np.array_equal(case.m.cpu().numpy(), case.m0)                     # not a synchronisation step
+    lc.lc_momentum_sync_ranges(case.m, case.m.stride(0), W, offsets, sizes, 3, 20, 10)
+    torch.cuda.synchronize()
+    got = case.m.cpu().numpy()
+    inside = np.zeros(n, bool)
+    for o, sz in zip(offsets, sizes):
+        inside[o:o + sz] = True
+        ref = orc.momentum_avg(case.m0[:, o:o + sz])
+        for w in range(W):
+            assert_close(got[w, o:o + sz], ref, "averaged range")
+    assert np.array_equal(got[:, ~inside], case.m0[:, ~inside])              # everything else untouched

@@ -526,3 +526,32 @@ def test_ternary_hand_case_and_difference_to_one_bit(hand):
     assert one["u"][:7].tolist() == r["u"][:7].tolist() and one["u"][7] == 1 and r["u"][7] == 0
     r4 = orc.step_ternary(theta, np.zeros((4, 8), np.float32), g, beta1=0.9, beta2=0.99, lr=1e-4, wd=0.0)
     assert r4["S"].tolist() == _ints(gold["step1.W4.S"])[:7] + [0]           # ties stay 0 by themselves
+
+
+# --------------------------------------------------------------------------------------
+# divergence metric of Section 5.1 (max over elements of the std across workers)
+# --------------------------------------------------------------------------------------
+def test_momentum_divergence_closed_forms():
+    rng = np.random.default_rng(17)
+    n = 400
+    a = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    b = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    # two workers: the std of {a, b} is |a - b| / 2
+    want = float(np.max(np.abs(a.astype(np.float64) - b) / 2))
+    assert orc.momentum_divergence(np.stack([a, b])) == pytest.approx(want, rel=1e-14)
+    assert orc.momentum_divergence(np.stack([a, a, a])) == 0.0                   # synchronised momenta
+    for W in (3, 8, 16):
+        m = (rng.standard_normal((W, n)) * 1e-3).astype(np.float32)
+        lib = float(np.max(np.std(m.astype(np.float64), axis=0)))              # library routine, ddof = 0
+        assert orc.momentum_divergence(m) == pytest.approx(lib, rel=1e-12)
+        assert orc.momentum_divergence(m * np.float32(4.0)) == pytest.approx(4 * lib, rel=1e-12)
+        shifted = m + np.float32(1.0)                                           # a common offset changes nothing
+        assert orc.momentum_divergence(shifted) == pytest.approx(
+            float(np.max(np.std(shifted.astype(np.float64), axis=0))), rel=1e-9)
+    # one element stands out: it alone sets the maximum ({0,0,0,1}: mean 1/4, std sqrt(3)/4)
+    m = np.zeros((4, 50), np.float32)
+    m[3, 7] = 1.0
+    assert orc.momentum_divergence(m) == pytest.approx(math.sqrt(3) / 4, rel=1e-15)
+    # averaging the momenta (Section 5) removes the divergence
+    avg = orc.momentum_avg(m).astype(np.float32)
+    assert orc.momentum_divergence(np.repeat(avg[None], 4, 0)) == 0.0
