@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--per-tensor", action="store_true",
                     help="1-bit workloads with a tensor list: one pair of calls per tensor instead of one per arena "
                          "(shows the small-tensor launch overhead; not the headline configuration)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (for odd and for even iterations) into HIP graphs and time replays; "
+                         "per-kernel timings are then not available and the roofline entry is for the whole step")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="also run one plain device copy of BYTES (read BYTES, write BYTES) before the steps: "
                          "the reference point for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -276,15 +279,38 @@ def main():
     for _ in range(args.warmup):
         one_step(False)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step(True)
-    torch.cuda.synchronize()
+    if args.graph:
+        side = torch.cuda.Stream()
+        graphs = {}
+        with torch.cuda.stream(side):
+            for parity in (1, 0):
+                step_no[0] = 2 - parity                      # 1 (odd) or 2 (even): only the parity matters
+                graphs[parity] = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graphs[parity], stream=side):
+                    for k in kernels:
+                        k.fn()
+        torch.cuda.synchronize()
+        for i in range(args.warmup):
+            graphs[(i + 1) % 2].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[(i + 1) % 2].replay()
+        torch.cuda.synchronize()
+    else:
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            one_step(True)
+        torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
 
     per_kernel = []
-    for k in kernels:
+    if args.graph:
+        tot = sum(k.alg_bytes for k in kernels)
+        per_kernel.append({"kernel": "whole step (graph replay)", "ms": ms_per_step, "alg_bytes": tot,
+                           "achieved_GBps": tot / (ms_per_step * 1e-3) / 1e9})
+    for k in ([] if args.graph else kernels):
         ms = k.mean_ms()
         per_kernel.append({"kernel": k.name, "ms": ms, "alg_bytes": k.alg_bytes,
                            "achieved_GBps": k.alg_bytes / (ms * 1e-3) / 1e9})
@@ -300,7 +326,8 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "n_params": wl.n, "workers": wl.W, "mode": wl.mode, "p": wl.p,
                    "g_dtype": wl.g_dtype, "momentum_avg": wl.momentum_avg, "levels": wl.levels,
-                   "calls": "per tensor" if args.per_tensor else "one flat arena"},
+                   "calls": "per tensor" if args.per_tensor else "one flat arena",
+                   "launch": "hip graph replay" if args.graph else "stream"},
         "step_alg_bytes": step_bytes, "step_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": roofline, "kernels": per_kernel,

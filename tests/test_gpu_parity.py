@@ -378,3 +378,54 @@ def test_momentum_sync_ranges_policy():
         for w in range(W):
             assert_close(got[w, o:o + sz], ref, "averaged range")
     assert np.array_equal(got[:, ~inside], case.m0[:, ~inside])              # everything else untouched
+
+
+def test_hip_graph_replay_matches_eager():
+    """The library only launches kernels (no memsets, no allocation, no synchronisation),
+    so a step can be captured into a HIP graph.  Several replays, with eager work and
+    synchronisations in between, must each equal the eager result bit for bit."""
+    n, W = 200000 + 77, 4
+    eager = Case(n, W, seed=16000, m_spread=1.0)
+    graph = Case(n, W, seed=16000, m_spread=1.0)
+    nw = nwords(n)
+    mean = torch.zeros(W, dtype=torch.float64, device="cuda")
+    ws = torch.zeros(W * lc.LC_L1_WORKSPACE_WORDS, dtype=torch.int64, device="cuda")
+    lv = torch.zeros((W, (n + 127) // 64 * 64), dtype=torch.uint8, device="cuda")
+
+    def step(case, q, stream):
+        lc.lc_local_update_pack(case.g, case.g.stride(0), case.gd, case.m, case.m.stride(0), W, n, HP["beta1"], 1,
+                                HP["beta2"], 1, q, q.stride(0), 1, lc.LC_ZERO_ALT, stream=stream)
+        lc.lc_vote_apply_1bit(q, q.stride(0) // 8, W, n, 1, lc.LC_TIE_ZERO, case.theta, HP["lr"], HP["wd"], None, 0, None,
+                              0, lc.LC_F32, 0, HP["beta2"], stream=stream)
+        lc.lc_l1_mean_abs(case.g, case.g.stride(0), case.gd, case.m, case.m.stride(0), W, n, HP["beta1"], mean, ws,
+                          stream=stream)                      # zeroes its workspace with a kernel, not a memset
+        lc.lc_l1_quantize_pack(case.g, case.g.stride(0), case.gd, case.m, case.m.stride(0), W, n, HP["beta1"], 0,
+                               HP["beta2"], 15, mean, lv, lv.stride(0), stream=stream)
+        lc.lc_momentum_avg(case.m, case.m.stride(0), W, n, stream=stream)
+
+    qe, qg = guarded(W, nw * 8, "cuda"), guarded(W, nw * 8, "cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(graph, qg, side)                                 # warm-up outside capture, then restore the state
+        side.synchronize()
+        graph.theta.copy_(torch.from_numpy(graph.theta0).cuda())
+        graph.m.copy_(torch.from_numpy(graph.m0).cuda())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step(graph, qg, side)
+    torch.cuda.synchronize()
+    for replay in range(4):
+        step(eager, qe, None)
+        lv_eager = lv.clone()
+        mean_eager = mean.clone()
+        torch.cuda.synchronize()
+        lv.zero_()
+        mean.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(qe, qg), "replay %d: packed words" % replay
+        assert torch.equal(eager.theta, graph.theta) and torch.equal(eager.m, graph.m), "replay %d" % replay
+        assert torch.equal(lv, lv_eager) and torch.equal(mean, mean_eager), "replay %d: L1 levels" % replay
+        busy = torch.randn(1 << 20, device="cuda").sum().item()          # eager work between replays
+        assert busy == busy
