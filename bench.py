@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--per-tensor", action="store_true",
                     help="1-bit workloads with a tensor list: one pair of calls per tensor instead of one per arena "
                          "(shows the small-tensor launch overhead; not the headline configuration)")
+    ap.add_argument("--groups", action="store_true",
+                    help="1-bit workloads with a tensor list: per-tensor learning rates through the one-launch "
+                         "group table (lc_vote_apply_1bit_groups) instead of one pair for the arena")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (for odd and for even iterations) into HIP graphs and time replays; "
                          "per-kernel timings are then not available and the roofline entry is for the whole step")
@@ -64,7 +67,7 @@ class Kernel:
         return sum(a.elapsed_time(b) for a, b in self.events) / max(1, len(self.events))
 
 
-def build_step(wl, torch, lc, synth, per_tensor=False):
+def build_step(wl, torch, lc, synth, per_tensor=False, groups=False):
     """Allocate the workload on cuda:0 and return (kernels, state) for one step."""
     dev = "cuda"
     n, W = wl.n, wl.W
@@ -118,11 +121,28 @@ def build_step(wl, torch, lc, synth, per_tensor=False):
             lambda: lc.lc_local_update_pack(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], 1, hp["beta2"], 1, q,
                                             q.stride(0) * 8, step_no[0], lc.LC_ZERO_ALT),
             W * n * (4 + gb + 4 + 1 / 8)))
-        kernels.append(Kernel(
-            "vote_apply_1bit",
-            lambda: lc.lc_vote_apply_1bit(q, q.stride(0), W, n, step_no[0], lc.LC_TIE_ZERO, theta, hp["lr"], hp["wd"],
-                                          None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
-            n * (W / 8 + 8)))
+        if groups and wl.tensors:
+            ends, off = [], 0
+            for _, sz in wl.tensors:
+                off += sz
+                ends.append(off // 64)
+            end64 = torch.tensor(ends, dtype=torch.int32, device=dev)
+            # matrices at the base rate, vectors (biases, LayerNorm) at 30x, no decay on vectors
+            is_vec = [sz < 8192 for _, sz in wl.tensors]
+            lr_t = torch.tensor([hp["lr"] * (30.0 if v else 1.0) for v in is_vec], dtype=torch.float32, device=dev)
+            wd_t = torch.tensor([0.0 if v else hp["wd"] for v in is_vec], dtype=torch.float32, device=dev)
+            st.update(end64=end64, lr_t=lr_t, wd_t=wd_t)
+            kernels.append(Kernel(
+                "vote_apply_1bit_groups",
+                lambda: lc.lc_vote_apply_1bit_groups(q, q.stride(0), W, n, step_no[0], lc.LC_TIE_ZERO, theta, end64,
+                                                     lr_t, wd_t, len(ends)),
+                n * (W / 8 + 8)))
+        else:
+            kernels.append(Kernel(
+                "vote_apply_1bit",
+                lambda: lc.lc_vote_apply_1bit(q, q.stride(0), W, n, step_no[0], lc.LC_TIE_ZERO, theta, hp["lr"],
+                                              hp["wd"], None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
+                n * (W / 8 + 8)))
     elif wl.mode == "ternary":
         pos = torch.zeros((W, synth.round_up(nw, 8)), dtype=torch.int64, device=dev)
         nz = torch.zeros((W, synth.round_up(nw, 8)), dtype=torch.int64, device=dev)
@@ -261,7 +281,7 @@ def main():
     lc.load()
     torch.cuda.set_device(0)
     wl = synth.workload(args.workload)
-    kernels, st, step_no = build_step(wl, torch, lc, synth, args.per_tensor)
+    kernels, st, step_no = build_step(wl, torch, lc, synth, args.per_tensor, args.groups)
     torch.cuda.synchronize()
     if args.copy_calibration:
         src = torch.empty(args.copy_calibration, dtype=torch.uint8, device="cuda").fill_(1)
@@ -326,7 +346,8 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "n_params": wl.n, "workers": wl.W, "mode": wl.mode, "p": wl.p,
                    "g_dtype": wl.g_dtype, "momentum_avg": wl.momentum_avg, "levels": wl.levels,
-                   "calls": "per tensor" if args.per_tensor else "one flat arena",
+                   "calls": "per tensor" if args.per_tensor else ("one flat arena, per-tensor rates" if args.groups
+                                                                  else "one flat arena"),
                    "launch": "hip graph replay" if args.graph else "stream"},
         "step_alg_bytes": step_bytes, "step_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -135,6 +135,18 @@ int lc_vote_apply_1bit(const uint64_t *q, size_t q_stride_words, int W, size_t n
                        size_t g_stride_elems, int g_dtype, int n_m, float beta2,
                        void *stream);
 
+/* lc_vote_apply_1bit with per-group learning rates and weight decays (Appendix F.3 scales
+ * the rate of the head, embedding and scalar parameter groups) in ONE launch over the
+ * whole arena: the range is cut into n_groups consecutive segments; segment s ends at
+ * element 64 * group_end64[s] (ascending; the last end must reach n) and uses
+ * group_lr[s], group_wd[s].  The three arrays live on the DEVICE (they are static for a
+ * model: upload once).  No momentum streams.  One call per tensor gives the same result
+ * but is launch-bound for small tensors. */
+int lc_vote_apply_1bit_groups(const uint64_t *q, size_t q_stride_words, int W, size_t n,
+                              uint64_t step, int tie_rule, float *theta,
+                              const uint32_t *group_end64, const float *group_lr,
+                              const float *group_wd, int n_groups, void *stream);
+
 /* lc_pbit_sum_sign followed by lc_apply_update without writing the planes; sum_out as
  * in lc_pbit_sum_sign (may be NULL). */
 int lc_pbit_sum_apply(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n,

@@ -34,6 +34,7 @@ SIGNATURES = {
     "lc_momentum_divergence": (_i, [_vp, _sz, _i, _sz, _vp, _vp]),
     "lc_momentum_sync_ranges": (_i, [_vp, _sz, _i, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), _i, _u64, _u64, _vp]),
     "lc_vote_apply_1bit": (_i, [_vp, _sz, _i, _sz, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
+    "lc_vote_apply_1bit_groups": (_i, [_vp, _sz, _i, _sz, _u64, _i, _vp, _vp, _vp, _vp, _i, _vp]),
     "lc_pbit_sum_apply": (_i, [_vp, _sz, _i, _i, _sz, _i, _vp, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i,
                                _f, _vp]),
     "lc_local_update_pack_ternary": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _i, _f, _vp, _vp, _sz, _vp]),
@@ -142,6 +143,12 @@ def lc_vote_apply_1bit(q, q_stride_words, W, n, step, tie_rule, theta, lr, wd, m
                        g_stride_elems, g_dtype, n_m, beta2, stream=None, check=True):
     return _call("lc_vote_apply_1bit", check, _ptr(q), q_stride_words, W, n, step, tie_rule, _ptr(theta), lr, wd,
                  _ptr(m), m_stride_elems, _ptr(g), g_stride_elems, g_dtype, n_m, beta2, _stream(stream))
+
+
+def lc_vote_apply_1bit_groups(q, q_stride_words, W, n, step, tie_rule, theta, group_end64, group_lr, group_wd,
+                              n_groups, stream=None, check=True):
+    return _call("lc_vote_apply_1bit_groups", check, _ptr(q), q_stride_words, W, n, step, tie_rule, _ptr(theta),
+                 _ptr(group_end64), _ptr(group_lr), _ptr(group_wd), n_groups, _stream(stream))
 
 
 def lc_pbit_sum_apply(q, q_stride_bytes, in_bits, W, n, p, sum_out, step, tie_rule, theta, lr, wd, m,

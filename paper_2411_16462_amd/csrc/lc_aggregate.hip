@@ -433,14 +433,43 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
     if (!(APPLY || KOUT)) return;
     const uint8_t *pos8 = reinterpret_cast<const uint8_t *>(s_pos[wave]);
     const uint8_t *nz8 = reinterpret_cast<const uint8_t *>(s_nz[wave]);
-    const float lr = P.lr, wd = P.wd;
     const int sh = (lane & 1) * 4;
+
+    // Learning rate and weight decay: one pair for the call, or one per parameter group.
+    // Groups are consecutive segments of the range that end at multiples of 64 elements,
+    // so the 4 elements of a lane always share a group.  The group of the wave's first
+    // element is found by bisection (uniform); lanes whose elements lie further on walk
+    // forward from there, which is rare.
+    int seg0 = 0;
+    if (APPLY && P.n_seg > 0) {
+        const uint32_t first = static_cast<uint32_t>(wave_base / 64);
+        int lo = 0, hi = P.n_seg - 1;  // first segment whose end lies beyond `first`
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (P.seg_end64[mid] > first) hi = mid;
+            else lo = mid + 1;
+        }
+        seg0 = lo;
+    }
+    auto rates = [&](size_t e, float &lr, float &wd) {
+        lr = P.lr;
+        wd = P.wd;
+        if (P.n_seg > 0) {
+            int sgm = seg0;
+            const uint32_t e64 = static_cast<uint32_t>(e / 64);
+            while (sgm < P.n_seg - 1 && e64 >= P.seg_end64[sgm]) ++sgm;
+            lr = P.seg_lr[sgm];
+            wd = P.seg_wd[sgm];
+        }
+    };
 
     if (APPLY && full_wave) {
 #pragma unroll
         for (int t = 0; t < kAggTiles; ++t) {
             const int byte = t * 32 + (lane >> 1);
             const uint32_t pn = pos8[byte] >> sh, zn = nz8[byte] >> sh;
+            float lr, wd;
+            rates(wave_base + t * 256 + lane * 4, lr, wd);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const float uf = ((zn >> k) & 1u) ? (((pn >> k) & 1u) ? 1.0f : -1.0f) : 0.0f;
@@ -483,6 +512,8 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
             if (e >= n) break;
             const int byte = t * 32 + (lane >> 1);
             const uint32_t pn = pos8[byte] >> sh, zn = nz8[byte] >> sh;
+            float lr, wd;
+            rates(e, lr, wd);
             for (int k = 0; k < 4 && e + k < n; ++k) {
                 const float uf = ((zn >> k) & 1u) ? (((pn >> k) & 1u) ? 1.0f : -1.0f) : 0.0f;
                 const float v = P.theta[e + k];

@@ -7,6 +7,13 @@ namespace lc {
 
 namespace {
 
+struct Groups {
+    const uint32_t *end64 = nullptr;
+    const float *lr = nullptr;
+    const float *wd = nullptr;
+    int n = 0;
+};
+
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline int from_hip(hipError_t e) { return e == hipSuccess ? LC_OK : -static_cast<int>(e); }
 inline size_t gbytes(int g_dtype) { return g_dtype == LC_BF16 ? 2 : 4; }
@@ -36,9 +43,11 @@ int tie_code(int tie_rule, uint64_t step)
 // shared by the four aggregation entry points
 int aggregate(const void *q, const void *q2, size_t q_stride_bytes, int in_bits, int W, size_t n, int p, int levels, void *sum_out, uint64_t *vote_pos,
               uint64_t *vote_nz, uint64_t step, int tie_rule, bool apply, float *theta, float lr, float wd, float *m,
-              size_t m_stride, const void *g, size_t g_stride, int g_dtype, int n_m, float beta2, void *stream)
+              size_t m_stride, const void *g, size_t g_stride, int g_dtype, int n_m, float beta2, void *stream,
+              const Groups &groups = Groups())
 {
     if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    if (groups.n < 0 || (groups.n > 0 && (!groups.end64 || !groups.lr || !groups.wd))) return groups.n < 0 ? LC_ERR_SIZE : LC_ERR_NULL;
     if (tie_rule != LC_TIE_ZERO && tie_rule != LC_TIE_ALT) return LC_ERR_MODE;
     int sum_bits = 0;
     if (levels != 0) {  // summed level bytes: every row holds level + L in [0, 2L]
@@ -87,6 +96,10 @@ int aggregate(const void *q, const void *q2, size_t q_stride_bytes, int in_bits,
     P.theta = theta;
     P.lr = lr;
     P.wd = wd;
+    P.seg_end64 = groups.end64;
+    P.seg_lr = groups.lr;
+    P.seg_wd = groups.wd;
+    P.n_seg = groups.n;
     P.m = m;
     P.m_stride = m_stride;
     P.g = g;
@@ -298,6 +311,20 @@ int lc_momentum_sync_ranges(float *m, size_t m_stride_elems, int W, const size_t
         if (e != hipSuccess) return from_hip(e);
     }
     return LC_OK;
+}
+
+int lc_vote_apply_1bit_groups(const uint64_t *q, size_t q_stride_words, int W, size_t n, uint64_t step, int tie_rule,
+                              float *theta, const uint32_t *group_end64, const float *group_lr, const float *group_wd,
+                              int n_groups, void *stream)
+{
+    if (n_groups < 1) return LC_ERR_SIZE;
+    Groups gr;
+    gr.end64 = group_end64;
+    gr.lr = group_lr;
+    gr.wd = group_wd;
+    gr.n = n_groups;
+    return aggregate(q, nullptr, q_stride_words * 8, 1, W, n, 0, 0, nullptr, nullptr, nullptr, step, tie_rule, true, theta,
+                     0.0f, 0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream, gr);
 }
 
 int lc_container_bits(int p) { return container(p); }

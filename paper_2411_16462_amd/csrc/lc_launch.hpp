@@ -23,6 +23,10 @@ struct AggParams {
     int tie_possible;       // K == thresh is a tie (even W for 0/1 votes; always for levels)
     float *theta;
     float lr, wd;
+    const uint32_t *seg_end64;  // parameter groups: end of each segment in units of 64 elements, ascending
+    const float *seg_lr;        // per-segment learning rate and weight decay (device arrays)
+    const float *seg_wd;
+    int n_seg;                  // 0: lr / wd above hold for the whole range
     float *m;
     size_t m_stride;
     const void *g;

@@ -429,3 +429,42 @@ def test_hip_graph_replay_matches_eager():
         assert torch.equal(lv, lv_eager) and torch.equal(mean, mean_eager), "replay %d: L1 levels" % replay
         busy = torch.randn(1 << 20, device="cuda").sum().item()          # eager work between replays
         assert busy == busy
+
+
+@pytest.mark.parametrize("ragged_tail", [0, 37])
+def test_groups_in_one_launch_equal_per_tensor_calls(ragged_tail):
+    """Per-group learning rate / weight decay: one launch with a device table of segments
+    against one call per tensor, and both against the oracle."""
+    sizes = [64 * 37, 768, 768 * 5, 64, 2304, 64 * 129, 768 * 3 + 64 * 2, 4096 * 3, 1024 + 64, 64 * 40 + ragged_tail]
+    lrs = [1e-4, 3e-3, 1e-4, 3e-2, 1e-4, 2e-4, 3e-3, 1e-4, 5e-5, 3e-3]
+    wds = [0.1, 0.0, 0.1, 0.01, 0.0, 0.1, 1.0, 0.1, 0.1, 0.0]
+    n, W = sum(sizes), 4
+    a = Case(n, W, seed=17000, m_scale=0.0)
+    b = Case(n, W, seed=17000, m_scale=0.0)
+    nw = nwords(n)
+    q = guarded(W, nw * 8, a.device)
+    lc.lc_local_update_pack(a.g, a.g.stride(0), a.gd, a.m, a.m.stride(0), W, n, HP["beta1"], 0, HP["beta2"], 1, q,
+                            q.stride(0), 2, lc.LC_ZERO_ALT)
+    ends, off = [], 0
+    for sz in sizes:
+        off += sz
+        ends.append((off + 63) // 64)
+    end64 = torch.tensor(ends, dtype=torch.int32, device="cuda")
+    lr_t = torch.tensor(lrs, dtype=torch.float32, device="cuda")
+    wd_t = torch.tensor(wds, dtype=torch.float32, device="cuda")
+    lc.lc_vote_apply_1bit_groups(q, q.stride(0) // 8, W, n, 2, lc.LC_TIE_ZERO, a.theta, end64, lr_t, wd_t, len(sizes))
+    off = 0
+    ref = oracle_step(a, HP, 2)
+    want = np.empty(n, np.float64)
+    for sz, lr, wd in zip(sizes, lrs, wds):
+        lc.lc_vote_apply_1bit(q[:, off // 8:], q.stride(0) // 8, W, sz, 2, lc.LC_TIE_ZERO, b.theta[off:], lr, wd, None, 0,
+                              None, 0, lc.LC_F32, 0, HP["beta2"])
+        want[off:off + sz] = orc.apply(a.theta0[off:off + sz], ref["u"][off:off + sz], lr, wd)
+        off += sz
+    torch.cuda.synchronize()
+    assert torch.equal(a.theta, b.theta)
+    assert_close(a.theta.cpu().numpy(), want, "theta with per-group rates")
+    assert lc.lc_vote_apply_1bit_groups(q, q.stride(0) // 8, W, n, 2, lc.LC_TIE_ZERO, a.theta, None, lr_t, wd_t, 3,
+                                        check=False) == lc.LC_ERR_NULL
+    assert lc.lc_vote_apply_1bit_groups(q, q.stride(0) // 8, W, n, 2, lc.LC_TIE_ZERO, a.theta, end64, lr_t, wd_t, 0,
+                                        check=False) == lc.LC_ERR_SIZE
