@@ -29,6 +29,23 @@ constexpr int kPackWave = kPackTiles * 256;           // elements per wave
 constexpr int kPackBlock = kPackWave * (kPackThreads / kWave);
 static_assert(kPackTiles >= 1 && kPackTiles <= 8, "a lane of each 8-lane group stores one tile's dword");
 
+// Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by index.  With
+// LC_PACK_XCD the workgroup index is remapped so that 4 consecutive tiles -- whose 1-bit
+// output shares one 128-byte line -- run on the same XCD.
+#ifndef LC_PACK_XCD
+#define LC_PACK_XCD 4  // consecutive tiles per XCD (a power of two; 0: no remapping)
+#endif
+__device__ __forceinline__ size_t pack_chunk_index(unsigned b, unsigned nblocks)
+{
+#if LC_PACK_XCD
+    constexpr unsigned G = LC_PACK_XCD, group = 8u * G;
+    const unsigned full = nblocks & ~(group - 1u);  // remap only whole groups of workgroups
+    if (b < full) return (b & ~(group - 1u)) + (b & 7u) * G + ((b >> 3) & (G - 1u));
+#endif
+    (void)nblocks;
+    return b;
+}
+
 // bit that a value of the interpolation c maps to: 1 if c > 0, 0 if c < 0, and the
 // zero rule's bit when c is zero (either sign) or NaN.
 __device__ __forceinline__ uint32_t sign_to_bit(float c, bool zero_is_one)
@@ -66,7 +83,7 @@ __global__ __launch_bounds__(kPackThreads) void local_update_pack_kernel(
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const size_t w = blockIdx.y;
-    const size_t wave_base = static_cast<size_t>(blockIdx.x) * kPackBlock + static_cast<size_t>(wave) * kPackWave;
+    const size_t wave_base = pack_chunk_index(blockIdx.x, gridDim.x) * kPackBlock + static_cast<size_t>(wave) * kPackWave;
     if (wave_base >= n) return;
 
     float *mrow = m + w * m_stride;
@@ -162,7 +179,7 @@ __global__ __launch_bounds__(kPackThreads) void local_update_pack_ternary_kernel
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const size_t w = blockIdx.y;
-    const size_t wave_base = static_cast<size_t>(blockIdx.x) * kPackBlock + static_cast<size_t>(wave) * kPackWave;
+    const size_t wave_base = pack_chunk_index(blockIdx.x, gridDim.x) * kPackBlock + static_cast<size_t>(wave) * kPackWave;
     if (wave_base >= n) return;
     float *mrow = m + w * m_stride;
     const void *grow = static_cast<const char *>(g) + w * g_stride * Grad<GDT>::kBytes;
