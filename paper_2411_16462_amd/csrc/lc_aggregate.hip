@@ -32,6 +32,9 @@ namespace lc {
 #ifndef LC_AGG_THREADS
 #define LC_AGG_THREADS 128
 #endif
+#ifndef LC_AGG_XCD
+#define LC_AGG_XCD 2  // consecutive workgroups per XCD (measured: +3..5 % on the W = 64 and p = 4 workloads)
+#endif
 constexpr int kAggThreads = LC_AGG_THREADS;   // workgroup size; waves are independent
 constexpr int kWaves = kAggThreads / kWave;
 #ifndef LC_AGG_WORDS
@@ -214,7 +217,7 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const size_t n = P.n;
-    const size_t wave_base = (static_cast<size_t>(blockIdx.x) * kWaves + wave) * kAggWave;
+    const size_t wave_base = (xcd_chunk_index<LC_AGG_XCD>(blockIdx.x, gridDim.x) * kWaves + wave) * kAggWave;
     if (wave_base >= n) return;
     const bool full_wave = wave_base + kAggWave <= n;
     const int W = P.W;

@@ -109,6 +109,22 @@ struct Grad<LC_BF16> {
 __device__ __forceinline__ f32x4 load4(const float *p) { return ld_stream(reinterpret_cast<const f32x4 *>(p)); }
 __device__ __forceinline__ void store4(float *p, f32x4 v) { st_stream(reinterpret_cast<f32x4 *>(p), v); }
 
+// Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by index.  This
+// remaps the workgroup index so that G consecutive chunks (G a power of two) run on the
+// same XCD; G = 0 or 1 leaves the order alone.  Only whole groups of 8 G workgroups are
+// remapped, so the map is a bijection for any grid size.
+template <unsigned G>
+__device__ __forceinline__ size_t xcd_chunk_index(unsigned b, unsigned nblocks)
+{
+    if constexpr (G > 1) {
+        constexpr unsigned group = 8u * G;
+        const unsigned full = nblocks & ~(group - 1u);
+        if (b < full) return (b & ~(group - 1u)) + (b & 7u) * G + ((b >> 3) & (G - 1u));
+    }
+    (void)nblocks;
+    return b;
+}
+
 // Algorithm 1 line 6 in fp32: one rounded product, one fused multiply-add.
 __device__ __forceinline__ float momentum_step(float m, float g, float beta2, float omb2)
 {

@@ -29,21 +29,14 @@ constexpr int kPackWave = kPackTiles * 256;           // elements per wave
 constexpr int kPackBlock = kPackWave * (kPackThreads / kWave);
 static_assert(kPackTiles >= 1 && kPackTiles <= 8, "a lane of each 8-lane group stores one tile's dword");
 
-// Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by index.  With
-// LC_PACK_XCD the workgroup index is remapped so that 4 consecutive tiles -- whose 1-bit
-// output shares one 128-byte line -- run on the same XCD.
+// The workgroup index is remapped so that 4 consecutive tiles -- whose 1-bit output shares
+// one 128-byte line -- run on the same XCD (measured: +1..3 %; 2 gains nothing, 8 and more lose).
 #ifndef LC_PACK_XCD
-#define LC_PACK_XCD 4  // consecutive tiles per XCD (a power of two; 0: no remapping)
+#define LC_PACK_XCD 4
 #endif
 __device__ __forceinline__ size_t pack_chunk_index(unsigned b, unsigned nblocks)
 {
-#if LC_PACK_XCD
-    constexpr unsigned G = LC_PACK_XCD, group = 8u * G;
-    const unsigned full = nblocks & ~(group - 1u);  // remap only whole groups of workgroups
-    if (b < full) return (b & ~(group - 1u)) + (b & 7u) * G + ((b >> 3) & (G - 1u));
-#endif
-    (void)nblocks;
-    return b;
+    return xcd_chunk_index<LC_PACK_XCD>(b, nblocks);
 }
 
 // bit that a value of the interpolation c maps to: 1 if c > 0, 0 if c < 0, and the
