@@ -560,6 +560,39 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
     }
 }
 
+// Vote only (planes out, nothing applied): the local reduction of the 1-bit compressed
+// allreduce between its all-to-all and its allgather (Section 3).  There is no element-wise
+// phase, so the word-per-lane layout is kept throughout: lane j of a wave owns word j of
+// every row (512 contiguous bytes per row and load instruction), a 256-thread workgroup
+// covers 256 words = 16384 elements -- enough bytes per workgroup not to be bound by the
+// dispatcher even for few workers.
+constexpr int kVoteThreads = 256;
+
+__global__ __launch_bounds__(kVoteThreads) void vote_only_kernel(const AggParams P)
+{
+    const size_t jw = static_cast<size_t>(blockIdx.x) * kVoteThreads + threadIdx.x;
+    const size_t n = P.n;
+    if (jw * 64 >= n) return;
+    const uint64_t vm = valid_mask(jw * 64, n);
+    const int W = P.W;
+    const size_t stride = P.q_stride_bytes / 8;
+    const uint64_t *qp = static_cast<const uint64_t *>(P.q) + jw;
+    uint64_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int w = 0;
+    for (; w + 8 <= W; w += 8) {
+        uint64_t x[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = ld_packed(qp + static_cast<size_t>(w + i) * stride);
+        csa8(c, x);
+    }
+    for (; w < W; ++w) ripple(c, ld_packed(qp + static_cast<size_t>(w) * stride), 0);
+    uint64_t gt, eq, pos, nz;
+    compare_planes(c, P.thresh, gt, eq);
+    vote_planes(gt, eq, P.tie_possible != 0, P.tie, pos, nz);
+    if (P.vote_pos) P.vote_pos[jw] = pos & vm;
+    if (P.vote_nz) P.vote_nz[jw] = nz & vm;
+}
+
 template <int IN, int GDT, bool APPLY, bool MOM, bool KOUT>
 static hipError_t launch_one(const AggParams &P, hipStream_t s)
 {
@@ -583,7 +616,13 @@ hipError_t launch_aggregate(const AggParams &P, int in_kind, bool apply, bool ko
 {
     switch (in_kind) {
     case IN_PLANES: return launch_in<IN_PLANES, false>(P, apply, g_dtype, s);
-    case IN_BITS: return kout ? launch_in<IN_BITS, true>(P, apply, g_dtype, s) : launch_in<IN_BITS, false>(P, apply, g_dtype, s);
+    case IN_BITS:
+        if (!apply && !kout) {
+            const size_t nw = (P.n + 63) / 64;
+            vote_only_kernel<<<static_cast<unsigned>((nw + kVoteThreads - 1) / kVoteThreads), kVoteThreads, 0, s>>>(P);
+            return hipGetLastError();
+        }
+        return kout ? launch_in<IN_BITS, true>(P, apply, g_dtype, s) : launch_in<IN_BITS, false>(P, apply, g_dtype, s);
     case IN_TERNARY: return launch_in<IN_TERNARY, false>(P, apply, g_dtype, s);
     case 2: return launch_in<2, false>(P, apply, g_dtype, s);
     case 4: return launch_in<4, false>(P, apply, g_dtype, s);
