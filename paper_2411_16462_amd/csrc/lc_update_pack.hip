@@ -5,14 +5,16 @@
 // 2 B), optionally writes m (4 B), and writes 1/8 .. 1 byte of packed output.
 //
 // Work split.  grid.y = worker, grid.x = chunk of kPackBlock elements.  A wave owns
-// kPackWave = 1024 consecutive elements as 4 tiles of 256: in a tile lane l holds
-// elements 4l..4l+3 (one 16-byte load per operand, 1 KiB per wave instruction), so the
-// wave's 1-bit output is exactly one 128-byte line.
+// kPackTiles tiles of 256 consecutive elements: in a tile lane l holds elements
+// 4l..4l+3 (one 16-byte load per operand, 1 KiB per wave instruction), so a tile's
+// 1-bit output is 32 bytes.  The default is one tile per wave and one wave per
+// workgroup: many short, independent waves measured fastest for this read-modify-write
+// stream (longer waves, 2..8 tiles, lose 3..10 %).
 //
 // 1-bit packing.  Each lane forms the 4 bits of its elements, shifts them to
 // 4*(l mod 8) and an OR butterfly over each aligned group of 8 lanes (three DPP steps)
 // leaves the dword that covers the group's 32 elements in every lane of the group.
-// Lanes 8h+t (t < 4) then store tile t's dword h: one 32-lane store per wave.
+// Lane 8h+t (t < kPackTiles) then stores tile t's dword h.
 #include "lc_launch.hpp"
 
 namespace lc {
