@@ -31,11 +31,11 @@ def parse():
     ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="parameters in the oracle's sample (0: skip)")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = host cores available, capped at 16")
     ap.add_argument("--per-tensor", action="store_true",
-                    help="1-bit workloads with a tensor list: one pair of calls per tensor instead of one per arena "
-                         "(shows the small-tensor launch overhead; not the headline configuration)")
+                    help="1-bit and L1 workloads with a tensor list: one set of calls per tensor instead of one per "
+                         "arena (shows the small-tensor launch overhead; not the headline configuration)")
     ap.add_argument("--groups", action="store_true",
-                    help="1-bit workloads with a tensor list: per-tensor learning rates through the one-launch "
-                         "group table (lc_vote_apply_1bit_groups) instead of one pair for the arena")
+                    help="1-bit and L1 workloads with a tensor list: per-tensor learning rates (and, for L1, per-tensor "
+                         "scales) through the group-table entry points, still one launch set for the arena")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (for odd and for even iterations) into HIP graphs and time replays; "
                          "per-kernel timings are then not available and the roofline entry is for the whole step")
@@ -164,20 +164,76 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False):
         mean = torch.zeros(W, dtype=torch.float64, device=dev)
         ws = torch.zeros(W * lc.LC_L1_WORKSPACE_WORDS, dtype=torch.int64, device=dev)
         st.update(q=q, sum_out=sum_out, mean_abs=mean)
-        kernels.append(Kernel(
-            "l1_mean_abs",
-            lambda: lc.lc_l1_mean_abs(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], mean, ws),
-            W * n * (4 + gb)))
-        kernels.append(Kernel(
-            "l1_quantize_pack",
-            lambda: lc.lc_l1_quantize_pack(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], 1, hp["beta2"], L, mean,
-                                           q, q.stride(0)),
-            W * n * (4 + gb + 4 + 1)))
-        kernels.append(Kernel(
-            "level_sum_apply",
-            lambda: lc.lc_level_sum_apply(q, q.stride(0), W, n, L, sum_out, step_no[0], lc.LC_TIE_ZERO, theta, hp["lr"],
-                                          hp["wd"], None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
-            n * (W + 1 + 8)))
+        if per_tensor and wl.tensors:
+            # one scale per tensor the slow way: three calls per tensor
+            spans, off = [], 0
+            for _, sz in wl.tensors:
+                assert sz % 64 == 0
+                spans.append((off, sz))
+                off += sz
+            mean_t = torch.zeros((len(spans), W), dtype=torch.float64, device=dev)
+            st["mean_abs"] = mean_t
+
+            def mean_all():
+                for k, (o, sz) in enumerate(spans):
+                    lc.lc_l1_mean_abs(g[:, o:], g.stride(0), gd, m[:, o:], m.stride(0), W, sz, hp["beta1"], mean_t[k], ws)
+
+            def quant_all():
+                for k, (o, sz) in enumerate(spans):
+                    lc.lc_l1_quantize_pack(g[:, o:], g.stride(0), gd, m[:, o:], m.stride(0), W, sz, hp["beta1"], 1,
+                                           hp["beta2"], L, mean_t[k], q[:, o:], q.stride(0))
+
+            def sum_all():
+                for o, sz in spans:
+                    lc.lc_level_sum_apply(q[:, o:], q.stride(0), W, sz, L, sum_out[o:], step_no[0], lc.LC_TIE_ZERO,
+                                          theta[o:], hp["lr"], hp["wd"], None, 0, None, 0, lc.LC_F32, 0, hp["beta2"])
+            kernels.append(Kernel("l1_mean_abs[per tensor]", mean_all, W * n * (4 + gb)))
+            kernels.append(Kernel("l1_quantize_pack[per tensor]", quant_all, W * n * (4 + gb + 4 + 1)))
+            kernels.append(Kernel("level_sum_apply[per tensor]", sum_all, n * (W + 1 + 8)))
+        elif groups and wl.tensors:
+            # one scale, rate and decay per tensor, three launches for the whole arena
+            ends, off = [], 0
+            for _, sz in wl.tensors:
+                off += sz
+                ends.append(off // 64)
+            G = len(ends)
+            end64 = torch.tensor(ends, dtype=torch.int32, device=dev)
+            is_vec = [sz < 8192 for _, sz in wl.tensors]
+            lr_t = torch.tensor([hp["lr"] * (30.0 if v else 1.0) for v in is_vec], dtype=torch.float32, device=dev)
+            wd_t = torch.tensor([0.0 if v else hp["wd"] for v in is_vec], dtype=torch.float32, device=dev)
+            mean_g = torch.zeros((W, G), dtype=torch.float64, device=dev)
+            ws_g = torch.zeros(lc.lc_l1_groups_workspace_words(W, G), dtype=torch.int64, device=dev)
+            st.update(end64=end64, lr_t=lr_t, wd_t=wd_t, mean_abs=mean_g)
+            kernels.append(Kernel(
+                "l1_mean_abs_groups",
+                lambda: lc.lc_l1_mean_abs_groups(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], end64, None, G,
+                                                 mean_g, ws_g),
+                W * n * (4 + gb)))
+            kernels.append(Kernel(
+                "l1_quantize_pack_groups",
+                lambda: lc.lc_l1_quantize_pack_groups(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], 1,
+                                                      hp["beta2"], L, end64, G, mean_g, q, q.stride(0)),
+                W * n * (4 + gb + 4 + 1)))
+            kernels.append(Kernel(
+                "level_sum_apply_groups",
+                lambda: lc.lc_level_sum_apply_groups(q, q.stride(0), W, n, L, sum_out, step_no[0], lc.LC_TIE_ZERO, theta,
+                                                     end64, lr_t, wd_t, G),
+                n * (W + 1 + 8)))
+        else:
+            kernels.append(Kernel(
+                "l1_mean_abs",
+                lambda: lc.lc_l1_mean_abs(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], mean, ws),
+                W * n * (4 + gb)))
+            kernels.append(Kernel(
+                "l1_quantize_pack",
+                lambda: lc.lc_l1_quantize_pack(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], 1, hp["beta2"], L, mean,
+                                               q, q.stride(0)),
+                W * n * (4 + gb + 4 + 1)))
+            kernels.append(Kernel(
+                "level_sum_apply",
+                lambda: lc.lc_level_sum_apply(q, q.stride(0), W, n, L, sum_out, step_no[0], lc.LC_TIE_ZERO, theta, hp["lr"],
+                                              hp["wd"], None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
+                n * (W + 1 + 8)))
     else:
         C = lc.lc_container_bits(wl.p)
         fb = (n * C + 7) // 8

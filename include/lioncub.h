@@ -197,6 +197,24 @@ int lc_l1_mean_abs(const void *g, size_t g_stride_elems, int g_dtype, const floa
                    size_t m_stride_elems, int W, size_t n, float beta1, double *mean_abs,
                    uint64_t *workspace, void *stream);
 
+/* Per-group scales in one call (a scale per parameter tensor, as when each tensor is
+ * quantised on its own): the range is cut into n_groups consecutive segments as in
+ * lc_vote_apply_1bit_groups (segment s ends at element 64 * group_end64[s], ascending, the
+ * last end reaches n; a segment may be empty), and mean_abs[w * n_groups + s] receives
+ * M_1 of worker w over segment s, formed exactly as in lc_l1_mean_abs.  group_count
+ * (device, n_groups uint64, may be NULL): the number of elements that the sum of segment
+ * s is divided by -- the tensor's true size when the arena pads tensors with zeros up to
+ * a multiple of 64; NULL divides by the segment's length.  A count or length of 0 gives
+ * 0.  workspace: lc_l1_groups_workspace_words(W, n_groups) uint64 on the device,
+ * overwritten.  group_end64 and group_count live on the DEVICE.  n_groups in
+ * 1..LC_MAX_GROUPS, n below 2^38. */
+#define LC_MAX_GROUPS (1 << 20)
+size_t lc_l1_groups_workspace_words(int W, int n_groups); /* host only; 0 if an argument is < 1 */
+int lc_l1_mean_abs_groups(const void *g, size_t g_stride_elems, int g_dtype, const float *m,
+                          size_t m_stride_elems, int W, size_t n, float beta1,
+                          const uint32_t *group_end64, const uint64_t *group_count,
+                          int n_groups, double *mean_abs, uint64_t *workspace, void *stream);
+
 /* Second pass: the scale L / (2 mean_abs[w]) is rounded to fp32, multiplied with c in
  * fp32, rounded to the nearest integer (ties to even), clamped to [-L, L] and stored as
  * the byte level + L: q row w receives n bytes.  mean_abs[w] = 0 (all of c is zero) gives
@@ -205,6 +223,15 @@ int lc_l1_quantize_pack(const void *g, size_t g_stride_elems, int g_dtype, float
                         size_t m_stride_elems, int W, size_t n, float beta1, int update_m,
                         float beta2, int levels, const double *mean_abs, uint8_t *q,
                         size_t q_stride_bytes, void *stream);
+
+/* lc_l1_quantize_pack with the scale of element i taken from mean_abs[w * n_groups + s]
+ * for the segment s that holds i (mean_abs as lc_l1_mean_abs_groups wrote it). */
+int lc_l1_quantize_pack_groups(const void *g, size_t g_stride_elems, int g_dtype, float *m,
+                               size_t m_stride_elems, int W, size_t n, float beta1,
+                               int update_m, float beta2, int levels,
+                               const uint32_t *group_end64, int n_groups,
+                               const double *mean_abs, uint8_t *q, size_t q_stride_bytes,
+                               void *stream);
 
 /* Sum of the W level bytes per element (sum_out, n bytes, may be NULL), and the sign of
  * the summed levels as vote planes; a zero sum follows tie_rule. */
@@ -217,6 +244,14 @@ int lc_level_sum_apply(const uint8_t *q, size_t q_stride_bytes, int W, size_t n,
                        uint8_t *sum_out, uint64_t step, int tie_rule, float *theta, float lr,
                        float wd, float *m, size_t m_stride_elems, const void *g,
                        size_t g_stride_elems, int g_dtype, int n_m, float beta2, void *stream);
+
+/* lc_level_sum_apply with per-group learning rates and weight decays, group arrays as in
+ * lc_vote_apply_1bit_groups; no momentum streams. */
+int lc_level_sum_apply_groups(const uint8_t *q, size_t q_stride_bytes, int W, size_t n,
+                              int levels, uint8_t *sum_out, uint64_t step, int tie_rule,
+                              float *theta, const uint32_t *group_end64,
+                              const float *group_lr, const float *group_wd, int n_groups,
+                              void *stream);
 
 /* Smallest field width of 1, 2, 4, 8 bits that holds a p-bit value; -1 if p is not in
  * 1..8.  Host only. */

@@ -19,6 +19,7 @@ LC_ZERO_ALT, LC_ZERO_POS, LC_ZERO_NEG = 0, 1, 2
 LC_TIE_ZERO, LC_TIE_ALT = 0, 1
 LC_MAX_W = 255
 LC_L1_WORKSPACE_WORDS = 384
+LC_MAX_GROUPS = 1 << 20
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblioncub.so")
 
@@ -42,6 +43,10 @@ SIGNATURES = {
     "lc_vote_apply_ternary": (_i, [_vp, _vp, _sz, _i, _sz, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
     "lc_l1_mean_abs": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _vp, _vp, _vp]),
     "lc_l1_quantize_pack": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _i, _f, _i, _vp, _vp, _sz, _vp]),
+    "lc_l1_groups_workspace_words": (_sz, [_i, _i]),
+    "lc_l1_mean_abs_groups": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _vp, _vp, _i, _vp, _vp, _vp]),
+    "lc_l1_quantize_pack_groups": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _i, _f, _i, _vp, _i, _vp, _vp, _sz, _vp]),
+    "lc_level_sum_apply_groups": (_i, [_vp, _sz, _i, _sz, _i, _vp, _u64, _i, _vp, _vp, _vp, _vp, _i, _vp]),
     "lc_level_sum_sign": (_i, [_vp, _sz, _i, _sz, _i, _vp, _vp, _vp, _u64, _i, _vp]),
     "lc_level_sum_apply": (_i, [_vp, _sz, _i, _sz, _i, _vp, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
     "lc_container_bits": (_i, [_i]),
@@ -185,6 +190,31 @@ def lc_l1_quantize_pack(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, bet
                         q, q_stride_bytes, stream=None, check=True):
     return _call("lc_l1_quantize_pack", check, _ptr(g), g_stride_elems, g_dtype, _ptr(m), m_stride_elems, W, n, beta1,
                  int(update_m), beta2, levels, _ptr(mean_abs), _ptr(q), q_stride_bytes, _stream(stream))
+
+
+def lc_l1_groups_workspace_words(W, n_groups):
+    return int(load().lc_l1_groups_workspace_words(W, n_groups))
+
+
+def lc_l1_mean_abs_groups(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, group_end64, group_count,
+                          n_groups, mean_abs, workspace, stream=None, check=True):
+    return _call("lc_l1_mean_abs_groups", check, _ptr(g), g_stride_elems, g_dtype, _ptr(m), m_stride_elems, W, n,
+                 beta1, _ptr(group_end64), _ptr(group_count), n_groups, _ptr(mean_abs), _ptr(workspace),
+                 _stream(stream))
+
+
+def lc_l1_quantize_pack_groups(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, update_m, beta2, levels,
+                               group_end64, n_groups, mean_abs, q, q_stride_bytes, stream=None, check=True):
+    return _call("lc_l1_quantize_pack_groups", check, _ptr(g), g_stride_elems, g_dtype, _ptr(m), m_stride_elems, W,
+                 n, beta1, int(update_m), beta2, levels, _ptr(group_end64), n_groups, _ptr(mean_abs), _ptr(q),
+                 q_stride_bytes, _stream(stream))
+
+
+def lc_level_sum_apply_groups(q, q_stride_bytes, W, n, levels, sum_out, step, tie_rule, theta, group_end64, group_lr,
+                              group_wd, n_groups, stream=None, check=True):
+    return _call("lc_level_sum_apply_groups", check, _ptr(q), q_stride_bytes, W, n, levels, _ptr(sum_out), step,
+                 tie_rule, _ptr(theta), _ptr(group_end64), _ptr(group_lr), _ptr(group_wd), n_groups,
+                 _stream(stream))
 
 
 def lc_level_sum_sign(q, q_stride_bytes, W, n, levels, sum_out, vote_pos, vote_nz, step, tie_rule, stream=None,

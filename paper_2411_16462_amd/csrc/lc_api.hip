@@ -222,6 +222,32 @@ int lc_l1_mean_abs(const void *g, size_t g_stride_elems, int g_dtype, const floa
     if (!mean_abs || !workspace) return LC_ERR_NULL;
     if (!aligned(mean_abs, 8) || !aligned(workspace, 8)) return LC_ERR_ALIGN;
     return from_hip(launch_l1_mean_abs(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, mean_abs, workspace,
+                                       L1Groups(), static_cast<hipStream_t>(stream)));
+}
+
+size_t lc_l1_groups_workspace_words(int W, int n_groups)
+{
+    if (W < 1 || n_groups < 1) return 0;
+    return static_cast<size_t>(W) * static_cast<size_t>(n_groups) * LC_L1_WORKSPACE_WORDS +
+           (static_cast<size_t>(n_groups) + 2) / 2;
+}
+
+int lc_l1_mean_abs_groups(const void *g, size_t g_stride_elems, int g_dtype, const float *m, size_t m_stride_elems, int W,
+                          size_t n, float beta1, const uint32_t *group_end64, const uint64_t *group_count, int n_groups,
+                          double *mean_abs, uint64_t *workspace, void *stream)
+{
+    if (W < 1 || W > LC_MAX_W || n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
+    if ((n + 63) / 64 > 0xFFFFFFFFull) return LC_ERR_SIZE;
+    const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
+    if (rc) return rc;
+    if (!mean_abs || !workspace || !group_end64) return LC_ERR_NULL;
+    if (!aligned(mean_abs, 8) || !aligned(workspace, 8) || !aligned(group_end64, 4) || !aligned(group_count, 8))
+        return LC_ERR_ALIGN;
+    L1Groups grp;
+    grp.end64 = group_end64;
+    grp.count = group_count;
+    grp.n = n_groups;
+    return from_hip(launch_l1_mean_abs(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, mean_abs, workspace, grp,
                                        static_cast<hipStream_t>(stream)));
 }
 
@@ -237,7 +263,27 @@ int lc_l1_quantize_pack(const void *g, size_t g_stride_elems, int g_dtype, float
     if (!aligned(mean_abs, 8) || !aligned(q, 16) || (W > 1 && q_stride_bytes % 16 != 0)) return LC_ERR_ALIGN;
     if (n == 0) return LC_OK;
     return from_hip(launch_l1_quantize_pack(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, update_m != 0, beta2,
-                                            levels, mean_abs, q, q_stride_bytes, static_cast<hipStream_t>(stream)));
+                                            levels, mean_abs, q, q_stride_bytes, L1Groups(), static_cast<hipStream_t>(stream)));
+}
+
+int lc_l1_quantize_pack_groups(const void *g, size_t g_stride_elems, int g_dtype, float *m, size_t m_stride_elems, int W,
+                               size_t n, float beta1, int update_m, float beta2, int levels, const uint32_t *group_end64,
+                               int n_groups, const double *mean_abs, uint8_t *q, size_t q_stride_bytes, void *stream)
+{
+    if (W < 1 || W > LC_MAX_W || n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
+    if ((n + 63) / 64 > 0xFFFFFFFFull) return LC_ERR_SIZE;
+    if (levels < 1 || levels > 127) return LC_ERR_RANGE;
+    const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
+    if (rc) return rc;
+    if (!mean_abs || !q || !group_end64) return LC_ERR_NULL;
+    if (!aligned(mean_abs, 8) || !aligned(q, 16) || (W > 1 && q_stride_bytes % 16 != 0) || !aligned(group_end64, 4))
+        return LC_ERR_ALIGN;
+    if (n == 0) return LC_OK;
+    L1Groups grp;
+    grp.end64 = group_end64;
+    grp.n = n_groups;
+    return from_hip(launch_l1_quantize_pack(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, update_m != 0, beta2,
+                                            levels, mean_abs, q, q_stride_bytes, grp, static_cast<hipStream_t>(stream)));
 }
 
 int lc_level_sum_sign(const uint8_t *q, size_t q_stride_bytes, int W, size_t n, int levels, uint8_t *sum_out,
@@ -255,6 +301,21 @@ int lc_level_sum_apply(const uint8_t *q, size_t q_stride_bytes, int W, size_t n,
     if (levels == 0) return LC_ERR_RANGE;
     return aggregate(q, nullptr, q_stride_bytes, 8, W, n, 0, levels, sum_out, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
                      m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
+}
+
+int lc_level_sum_apply_groups(const uint8_t *q, size_t q_stride_bytes, int W, size_t n, int levels, uint8_t *sum_out,
+                              uint64_t step, int tie_rule, float *theta, const uint32_t *group_end64, const float *group_lr,
+                              const float *group_wd, int n_groups, void *stream)
+{
+    if (levels == 0) return LC_ERR_RANGE;
+    if (n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
+    Groups grp;
+    grp.end64 = group_end64;
+    grp.lr = group_lr;
+    grp.wd = group_wd;
+    grp.n = n_groups;
+    return aggregate(q, nullptr, q_stride_bytes, 8, W, n, 0, levels, sum_out, nullptr, nullptr, step, tie_rule, true, theta, 0.0f,
+                     0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream, grp);
 }
 
 int lc_local_update_pack_ternary(const void *g, size_t g_stride_elems, int g_dtype, float *m, size_t m_stride_elems, int W,

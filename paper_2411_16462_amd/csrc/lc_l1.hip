@@ -17,6 +17,14 @@
 // limbs in LDS; the workgroup adds its limbs, carries propagated, to the worker's limbs
 // in global memory with 64-bit atomics.  A one-thread kernel rounds the long integer once to fp64
 // (nearest, ties to even) and divides by n.
+//
+// Groups.  With a table of parameter groups (consecutive segments of the arena that end on
+// multiples of 64 elements) every (worker, group) pair gets its own M_1 in the same three
+// launches: a one-workgroup kernel turns the segment ends into a running count of
+// workgroups per group (the "plan"), each workgroup of the summing kernel bisects the plan
+// for its group and works inside that segment only, and the finalising kernel runs one
+// thread per pair.  The second pass looks the group of each 64-element block up by
+// bisection on the segment ends while its loads of m and g are in flight.
 #include "lc_launch.hpp"
 
 namespace lc {
@@ -92,10 +100,57 @@ __device__ __forceinline__ void limbs_add(uint64_t *limbs, uint64_t value, uint3
     if (p2) atomicAdd(reinterpret_cast<unsigned long long *>(limbs + l + 2), static_cast<unsigned long long>(p2));
 }
 
-__global__ void l1_zero_kernel(uint64_t *workspace, int words)
+__global__ void l1_zero_kernel(uint64_t *workspace, size_t words)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i < words) workspace[i] = 0;
+}
+
+// Segment s of a group table covers the 64-element blocks [seg_lo64, seg_hi64); ends beyond
+// the arena are clamped, ends that do not ascend give an empty segment.
+__device__ __forceinline__ uint32_t seg_lo64(const uint32_t *end64, int s, uint32_t n64)
+{
+    if (s == 0) return 0u;
+    const uint32_t v = end64[s - 1];
+    return v < n64 ? v : n64;
+}
+__device__ __forceinline__ uint32_t seg_hi64(const uint32_t *end64, int s, uint32_t n64)
+{
+    const uint32_t v = end64[s];
+    const uint32_t hi = v < n64 ? v : n64, lo = seg_lo64(end64, s, n64);
+    return hi > lo ? hi : lo;
+}
+
+// plan[s] = number of summing workgroups of the groups before s, plan[G] = their total.
+// One workgroup: each thread adds a contiguous share of the groups, thread 0 scans the
+// shares.
+constexpr uint32_t kL1Block64 = kL1Block / 64;
+__global__ __launch_bounds__(256) void l1_plan_kernel(const uint32_t *__restrict__ end64, int G, uint32_t n64,
+                                                      uint32_t *__restrict__ plan)
+{
+    __shared__ uint32_t part[256];
+    const int per = (G + 255) / 256;
+    const int lo = static_cast<int>(threadIdx.x) * per;
+    const int hi = lo + per < G ? lo + per : G;
+    uint32_t sum = 0;
+    for (int s = lo; s < hi; ++s) sum += (seg_hi64(end64, s, n64) - seg_lo64(end64, s, n64) + kL1Block64 - 1) / kL1Block64;
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (int i = 0; i < 256; ++i) {
+            const uint32_t t = part[i];
+            part[i] = run;
+            run += t;
+        }
+        plan[G] = run;
+    }
+    __syncthreads();
+    uint32_t run = part[threadIdx.x];
+    for (int s = lo; s < hi; ++s) {
+        plan[s] = run;
+        run += (seg_hi64(end64, s, n64) - seg_lo64(end64, s, n64) + kL1Block64 - 1) / kL1Block64;
+    }
 }
 
 // How far above the wave's base position a magnitude may sit to take the fast path: a
@@ -104,21 +159,42 @@ __global__ void l1_zero_kernel(uint64_t *workspace, int words)
 constexpr uint32_t kL1Window = 28;
 static_assert(kL1Tiles * 4 <= 32, "lane sums must stay below 2^57");
 
-template <int GDT>
+template <int GDT, bool GROUPED>
 __global__ __launch_bounds__(kL1Threads) void l1_abs_sum_kernel(const void *__restrict__ g, size_t g_stride,
-                                                                const float *__restrict__ m, size_t m_stride, size_t n,
-                                                                float beta1, float omb1, uint64_t *__restrict__ workspace)
+                                                                const float *__restrict__ m, size_t m_stride, size_t n_all,
+                                                                float beta1, float omb1, uint64_t *__restrict__ workspace,
+                                                                const uint32_t *__restrict__ end64,
+                                                                const uint32_t *__restrict__ plan, int G)
 {
     __shared__ uint64_t s_limbs[kL1Limbs];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const size_t w = blockIdx.y;
+
+    // the range [first, n) this workgroup's accumulator covers, and which accumulator
+    size_t first = 0, n = n_all, acc = w;
+    uint32_t local_block = blockIdx.x;
+    if (GROUPED) {
+        if (blockIdx.x >= plan[G]) return;  // the grid is an upper bound; uniform in the workgroup
+        int lo = 0, hi = G;                 // last group whose first workgroup is <= blockIdx.x
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (plan[mid] <= blockIdx.x) lo = mid;
+            else hi = mid;
+        }
+        const uint32_t n64 = static_cast<uint32_t>((n_all + 63) / 64);
+        first = static_cast<size_t>(seg_lo64(end64, lo, n64)) * 64;
+        const size_t last = static_cast<size_t>(seg_hi64(end64, lo, n64)) * 64;
+        n = last < n_all ? last : n_all;
+        local_block = blockIdx.x - plan[lo];
+        acc = w * static_cast<size_t>(G) + static_cast<size_t>(lo);
+    }
     if (threadIdx.x < kL1Limbs) s_limbs[threadIdx.x] = 0;
     __syncthreads();
 
     const float *mrow = m + w * m_stride;
     const void *grow = static_cast<const char *>(g) + w * g_stride * Grad<GDT>::kBytes;
-    const size_t wave_base = static_cast<size_t>(blockIdx.x) * kL1Block + static_cast<size_t>(wave) * (kL1Tiles * 256);
+    const size_t wave_base = first + static_cast<size_t>(local_block) * kL1Block + static_cast<size_t>(wave) * (kL1Tiles * 256);
 
     // The wave's base position comes from its first tile: 22 binary orders below that
     // tile's largest magnitude, so the window reaches 64 times above it.  Elements outside
@@ -184,7 +260,7 @@ __global__ __launch_bounds__(kL1Threads) void l1_abs_sum_kernel(const void *__re
         // one of kL1Slots accumulators per worker, so that the atomics of neighbouring
         // workgroups do not queue on the same addresses
         uint64_t carry = 0;
-        uint64_t *dst = workspace + (w * kL1Slots + blockIdx.x % kL1Slots) * kL1Limbs;
+        uint64_t *dst = workspace + (acc * kL1Slots + blockIdx.x % kL1Slots) * kL1Limbs;
 #pragma unroll
         for (int l = 0; l < kL1Limbs; ++l) {
             const uint64_t v = s_limbs[l] + carry;
@@ -195,12 +271,27 @@ __global__ __launch_bounds__(kL1Threads) void l1_abs_sum_kernel(const void *__re
     }
 }
 
-// One thread per worker: the limbs as one integer (units of 2^-149), rounded once to
-// fp64 (nearest, ties to even), divided by n.
-__global__ void l1_finalize_kernel(uint64_t *workspace, int W, size_t n, double *mean_abs)
+// One thread per accumulator (worker, or worker x group when G > 0): the limbs as one
+// integer (units of 2^-149), rounded once to fp64 (nearest, ties to even), divided by the
+// element count (of the call; of the group's segment; or the caller's count for the group).
+__global__ void l1_finalize_kernel(uint64_t *workspace, int n_acc, size_t n_all, double *mean_abs, const uint32_t *end64,
+                                   const uint64_t *count, int G)
 {
     const int w = blockIdx.x * blockDim.x + threadIdx.x;
-    if (w >= W) return;
+    if (w >= n_acc) return;
+    size_t n = n_all;
+    if (G > 0) {
+        const int s = w % G;
+        if (count) {
+            n = count[s];
+        } else {
+            const uint32_t n64 = static_cast<uint32_t>((n_all + 63) / 64);
+            const size_t lo = static_cast<size_t>(seg_lo64(end64, s, n64)) * 64;
+            size_t hi = static_cast<size_t>(seg_hi64(end64, s, n64)) * 64;
+            hi = hi < n_all ? hi : n_all;
+            n = hi - lo;
+        }
+    }
     uint64_t *limb = workspace + static_cast<size_t>(w) * kL1Slots * kL1Limbs;  // slot 0 receives the total
     for (int s = 1; s < kL1Slots; ++s)
         for (int l = 0; l < kL1Limbs; ++l) limb[l] += limb[s * kL1Limbs + l];
@@ -241,19 +332,35 @@ __global__ void l1_finalize_kernel(uint64_t *workspace, int W, size_t n, double 
 }
 
 hipError_t launch_l1_mean_abs(const void *g, size_t g_stride, int g_dtype, const float *m, size_t m_stride, int W, size_t n,
-                              float beta1, double *mean_abs, uint64_t *workspace, hipStream_t s)
+                              float beta1, double *mean_abs, uint64_t *workspace, const L1Groups &grp, hipStream_t s)
 {
-    const int words = W * kL1Slots * kL1Limbs;
-    l1_zero_kernel<<<(words + 255) / 256, 256, 0, s>>>(workspace, words);
+    const int G = grp.n;
+    const size_t n_acc = static_cast<size_t>(W) * static_cast<size_t>(G > 0 ? G : 1);
+    const size_t words = n_acc * kL1Slots * kL1Limbs;
+    uint32_t *plan = reinterpret_cast<uint32_t *>(workspace + words);
+    l1_zero_kernel<<<static_cast<unsigned>((words + 255) / 256), 256, 0, s>>>(workspace, words);
     if (n > 0) {
-        const dim3 grid(static_cast<unsigned>((n + kL1Block - 1) / kL1Block), static_cast<unsigned>(W));
         const float omb1 = 1.0f - beta1;
-        if (g_dtype == LC_BF16)
-            l1_abs_sum_kernel<LC_BF16><<<grid, kL1Threads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, workspace);
-        else
-            l1_abs_sum_kernel<LC_F32><<<grid, kL1Threads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, workspace);
+        size_t blocks = (n + kL1Block - 1) / kL1Block;
+        if (G > 0) {
+            blocks += static_cast<size_t>(G);  // every group may end in a partly filled workgroup
+            l1_plan_kernel<<<1, 256, 0, s>>>(grp.end64, G, static_cast<uint32_t>((n + 63) / 64), plan);
+        }
+        const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>(W));
+#define LC_LAUNCH(GDT, GROUPED)                                                                                        \
+    l1_abs_sum_kernel<GDT, GROUPED><<<grid, kL1Threads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, workspace, \
+                                                                grp.end64, plan, G)
+        if (g_dtype == LC_BF16) {
+            if (G > 0) LC_LAUNCH(LC_BF16, true);
+            else LC_LAUNCH(LC_BF16, false);
+        } else {
+            if (G > 0) LC_LAUNCH(LC_F32, true);
+            else LC_LAUNCH(LC_F32, false);
+        }
+#undef LC_LAUNCH
     }
-    l1_finalize_kernel<<<(W + 63) / 64, 64, 0, s>>>(workspace, W, n, mean_abs);
+    l1_finalize_kernel<<<static_cast<unsigned>((n_acc + 63) / 64), 64, 0, s>>>(workspace, static_cast<int>(n_acc), n, mean_abs,
+                                                                               grp.end64, grp.count, G);
     return hipGetLastError();
 }
 
@@ -263,36 +370,62 @@ hipError_t launch_l1_mean_abs(const void *g, size_t g_stride, int g_dtype, const
 #endif
 constexpr int kQuantThreads = 64;  // one wave, one 256-element tile: same shape as the 1-bit pack kernel
 
-template <int GDT, bool UPDATE_M>
+// Level of one element: scale * c rounded to the nearest integer (ties to even), clamped.
+__device__ __forceinline__ int l1_level(float c, float scale, float fl, bool live)
+{
+    float r = __builtin_rintf(scale * c);
+    r = r > fl ? fl : r;
+    r = r < -fl ? -fl : r;
+    return live ? static_cast<int>(r) : 0;
+}
+
+template <int GDT, bool UPDATE_M, bool GROUPED>
 __global__ __launch_bounds__(kQuantThreads) void l1_quantize_pack_kernel(const void *__restrict__ g, size_t g_stride,
                                                                          float *__restrict__ m, size_t m_stride, size_t n,
                                                                          float beta1, float omb1, float beta2, float omb2,
                                                                          int L, const double *__restrict__ mean_abs,
-                                                                         uint8_t *__restrict__ q, size_t q_stride_bytes)
+                                                                         uint8_t *__restrict__ q, size_t q_stride_bytes,
+                                                                         const uint32_t *__restrict__ end64, int G)
 {
     const int lane = threadIdx.x;
     const size_t w = blockIdx.y;
-    const size_t e = xcd_chunk_index<LC_L1Q_XCD>(blockIdx.x, gridDim.x) * 256 + lane * 4;
+    const size_t tile = xcd_chunk_index<LC_L1Q_XCD>(blockIdx.x, gridDim.x) * 256;
+    const size_t e = tile + lane * 4;
     if (e >= n) return;
-    const double mean = mean_abs[w];
-    const bool live = mean > 0.0;                       // all-zero input: every level is 0
-    const float scale = live ? static_cast<float>(static_cast<double>(L) / (2.0 * mean)) : 0.0f;
-    const float fl = static_cast<float>(L);
     float *mrow = m + w * m_stride;
     const void *grow = static_cast<const char *>(g) + w * g_stride * Grad<GDT>::kBytes;
     uint8_t *qrow = q + w * q_stride_bytes;
-    if (e + 4 <= n) {
-        f32x4 mv = load4(mrow + e);
-        const f32x4 gv = Grad<GDT>::load4(grow, e);
+    const bool full = e + 4 <= n;
+    f32x4 mv = {0.0f, 0.0f, 0.0f, 0.0f}, gv = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (full) {  // issued first: the group look-up below runs while these are in flight
+        mv = load4(mrow + e);
+        gv = Grad<GDT>::load4(grow, e);
+    }
+    size_t mean_index = w;
+    if (GROUPED) {
+        // first group that ends beyond the tile's first 64-element block (uniform), then
+        // each lane walks on to the group of its own block
+        const uint32_t t64 = static_cast<uint32_t>(tile / 64);
+        int lo = 0, hi = G - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (end64[mid] > t64) hi = mid;
+            else lo = mid + 1;
+        }
+        const uint32_t e64 = static_cast<uint32_t>(e / 64);
+        while (lo < G - 1 && e64 >= end64[lo]) ++lo;
+        mean_index = w * static_cast<size_t>(G) + static_cast<size_t>(lo);
+    }
+    const double mean = mean_abs[mean_index];
+    const bool live = mean > 0.0;                       // all-zero input: every level is 0
+    const float scale = live ? static_cast<float>(static_cast<double>(L) / (2.0 * mean)) : 0.0f;
+    const float fl = static_cast<float>(L);
+    if (full) {
         uint32_t bytes = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const float c = interpolate_c(mv[k], gv[k], beta1, omb1);
-            float r = __builtin_rintf(scale * c);
-            r = r > fl ? fl : r;
-            r = r < -fl ? -fl : r;
-            const int level = live ? static_cast<int>(r) : 0;
-            bytes |= static_cast<uint32_t>(level + L) << (8 * k);
+            bytes |= static_cast<uint32_t>(l1_level(c, scale, fl, live) + L) << (8 * k);
             if (UPDATE_M) mv[k] = momentum_step(mv[k], gv[k], beta2, omb2);
         }
         if (UPDATE_M) store4(mrow + e, mv);
@@ -302,11 +435,7 @@ __global__ __launch_bounds__(kQuantThreads) void l1_quantize_pack_kernel(const v
             const float mm = mrow[e + k];
             const float gg = Grad<GDT>::load1(grow, e + k);
             const float c = interpolate_c(mm, gg, beta1, omb1);
-            float r = __builtin_rintf(scale * c);
-            r = r > fl ? fl : r;
-            r = r < -fl ? -fl : r;
-            const int level = live ? static_cast<int>(r) : 0;
-            qrow[e + k] = static_cast<uint8_t>(level + L);
+            qrow[e + k] = static_cast<uint8_t>(l1_level(c, scale, fl, live) + L);
             if (UPDATE_M) mrow[e + k] = momentum_step(mm, gg, beta2, omb2);
         }
     }
@@ -314,20 +443,25 @@ __global__ __launch_bounds__(kQuantThreads) void l1_quantize_pack_kernel(const v
 
 hipError_t launch_l1_quantize_pack(const void *g, size_t g_stride, int g_dtype, float *m, size_t m_stride, int W, size_t n,
                                    float beta1, bool update_m, float beta2, int levels, const double *mean_abs, uint8_t *q,
-                                   size_t q_stride_bytes, hipStream_t s)
+                                   size_t q_stride_bytes, const L1Groups &grp, hipStream_t s)
 {
     const dim3 grid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(W));
     const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
-#define LC_LAUNCH(GDT, UPD)                                                                                                  \
-    l1_quantize_pack_kernel<GDT, UPD><<<grid, kQuantThreads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, beta2, omb2, \
-                                                                     levels, mean_abs, q, q_stride_bytes)
+#define LC_LAUNCH(GDT, UPD, GRP)                                                                                        \
+    l1_quantize_pack_kernel<GDT, UPD, GRP><<<grid, kQuantThreads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1,    \
+                                                                          beta2, omb2, levels, mean_abs, q,            \
+                                                                          q_stride_bytes, grp.end64, grp.n)
+#define LC_LAUNCH2(GDT, UPD)             \
+    if (grp.n > 0) LC_LAUNCH(GDT, UPD, true); \
+    else LC_LAUNCH(GDT, UPD, false)
     if (g_dtype == LC_BF16) {
-        if (update_m) LC_LAUNCH(LC_BF16, true);
-        else LC_LAUNCH(LC_BF16, false);
+        if (update_m) { LC_LAUNCH2(LC_BF16, true); }
+        else { LC_LAUNCH2(LC_BF16, false); }
     } else {
-        if (update_m) LC_LAUNCH(LC_F32, true);
-        else LC_LAUNCH(LC_F32, false);
+        if (update_m) { LC_LAUNCH2(LC_F32, true); }
+        else { LC_LAUNCH2(LC_F32, false); }
     }
+#undef LC_LAUNCH2
 #undef LC_LAUNCH
     return hipGetLastError();
 }

@@ -52,10 +52,17 @@ hipError_t launch_local_update_pack_ternary(const void *g, size_t g_stride, int 
 constexpr int kL1Limbs = 12;  // 64-bit accumulators, 32 bits apart
 constexpr int kL1Slots = 32;  // independent sets of limbs per worker (spreads the atomics)
 static_assert(kL1Limbs * kL1Slots == LC_L1_WORKSPACE_WORDS, "workspace size in the header");
+// Optional table of parameter groups for the L1 calls (n = 0: none).  Segment s ends at
+// element 64 * end64[s]; count[s], if given, is the number of elements its mean divides by.
+struct L1Groups {
+    const uint32_t *end64 = nullptr;
+    const uint64_t *count = nullptr;
+    int n = 0;
+};
 hipError_t launch_l1_mean_abs(const void *g, size_t g_stride, int g_dtype, const float *m, size_t m_stride, int W, size_t n,
-                              float beta1, double *mean_abs, uint64_t *workspace, hipStream_t s);
+                              float beta1, double *mean_abs, uint64_t *workspace, const L1Groups &grp, hipStream_t s);
 hipError_t launch_l1_quantize_pack(const void *g, size_t g_stride, int g_dtype, float *m, size_t m_stride, int W, size_t n,
                                    float beta1, bool update_m, float beta2, int levels, const double *mean_abs, uint8_t *q,
-                                   size_t q_stride_bytes, hipStream_t s);
+                                   size_t q_stride_bytes, const L1Groups &grp, hipStream_t s);
 
 }  // namespace lc

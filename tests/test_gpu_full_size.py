@@ -183,3 +183,48 @@ def test_l1_workload():
     d = (st["theta"] - theta0 * (1.0 - wl.lr * wl.wd)) / wl.lr + u_all
     assert float(d.abs().max()) < 1e-2 and int(K_all.max()) <= 2 * L * W
     assert int(st["q"][:, :n].max()) <= 2 * L
+
+
+def test_l1_workload_per_tensor_scales():
+    """The same workload with one scale, rate and decay per tensor through the group-table
+    calls (bench.py --groups): every one of the 148 x 8 means is compared over all of its
+    elements, levels, sums and theta on sampled windows against the oracle applied tensor by
+    tensor."""
+    wl = synth.workload("l1")
+    kernels, st, step_no = bench.build_step(wl, torch, lc, synth, groups=True)
+    n, W, L = wl.n, wl.W, wl.levels
+    theta0 = st["theta"].clone()
+    m0 = torch.empty((W, n), dtype=torch.float32, device="cuda")
+    m0.copy_(st["m"])
+    for k in kernels:
+        k.fn()
+    torch.cuda.synchronize()
+    ends = (st["end64"].cpu().numpy().astype(np.int64) * 64).tolist()
+    starts = [0] + ends[:-1]
+    assert ends[-1] == n and len(ends) == len(wl.tensors)
+    means = st["mean_abs"].cpu().numpy()
+    lr_t, wd_t = st["lr_t"].cpu().numpy(), st["wd_t"].cpu().numpy()
+    for w in range(W):
+        c = orc.local_c(m0[w].cpu().numpy(), st["g"][w].cpu().numpy(), wl.beta1)
+        for s, (lo, hi) in enumerate(zip(starts, ends)):
+            assert orc.mean_abs(c[lo:hi]) == means[w, s], "worker %d, tensor %s" % (w, wl.tensors[s][0])
+        del c
+    # windows: the sampled ones plus one around every 16th tensor boundary
+    spans = windows(n, wl.seed) + [(max(0, e - 2048), min(n, e + 2048)) for e in ends[::16]]
+    for lo, hi in spans:
+        mm, gg = host_rows(m0, lo, hi), host_rows(st["g"], lo, hi)
+        seg = np.searchsorted(np.asarray(ends), np.arange(lo, hi), side="right")
+        fields = np.empty((W, hi - lo), np.uint8)
+        theta_ref = theta0[lo:hi].cpu().numpy().copy()
+        for s in np.unique(seg):
+            sel = np.flatnonzero(seg == s)
+            a, b = int(sel[0]), int(sel[-1]) + 1
+            for w in range(W):
+                lev = orc.l1_levels(orc.local_c(mm[w, a:b], gg[w, a:b], wl.beta1), means[w, s], L)
+                fields[w, a:b] = (lev.astype(np.int16) + L).astype(np.uint8)
+            K, S, u = orc.level_sum_sign(fields[:, a:b], L, step_no[0], orc.TIE_ZERO)
+            assert np.array_equal(st["sum_out"][lo + a:lo + b].cpu().numpy().astype(np.int32), K)
+            theta_ref[a:b] = orc.apply(theta_ref[a:b], u, float(lr_t[s]), float(wd_t[s]))
+        assert np.array_equal(st["q"][:, lo:hi].cpu().numpy(), fields), "level bytes in [%d, %d)" % (lo, hi)
+        assert_close(st["theta"][lo:hi].cpu().numpy(), theta_ref, "theta in [%d, %d)" % (lo, hi))
+    assert int(st["q"][:, :n].max()) <= 2 * L and int(st["sum_out"][:n].max()) <= 2 * L * W

@@ -8,6 +8,7 @@ import torch
 import oracle as orc
 import paper_2411_16462_amd as lc
 from harness import SENTINEL, Case, assert_close, guarded, untouched, words_of
+from paper_2411_16462_amd import synth
 
 pytestmark = pytest.mark.gpu
 
@@ -141,3 +142,164 @@ def test_l1_mean_is_reproducible_and_order_free():
         outs.append(mean.cpu().numpy())
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
     assert outs[0][0] == orc.mean_abs(case.g0[0])                            # beta1 = 0, m = 0: c = g
+
+
+# ---- per-group scales in one call ---------------------------------------------------------
+def segments_of(ends64, n):
+    """[(lo, hi)] element ranges of a group table, as the C ABI defines them."""
+    n64 = (n + 63) // 64
+    out, prev = [], 0
+    for e in ends64:
+        lo = min(prev, n64)
+        hi = max(min(e, n64), lo)
+        out.append((lo * 64, min(hi * 64, n)))
+        prev = e
+    return out
+
+
+def run_l1_groups(case, L, step, ends64, counts=None, lr=None, wd=None, tie=lc.LC_TIE_ZERO):
+    n, W, G = case.n, case.W, len(ends64)
+    dev = case.device
+    end_t = torch.tensor(ends64, dtype=torch.int32, device=dev)
+    cnt_t = None if counts is None else torch.tensor(counts, dtype=torch.int64, device=dev)
+    mean = torch.full((W, G), -1.0, dtype=torch.float64, device=dev)
+    ws = torch.full((lc.lc_l1_groups_workspace_words(W, G),), -1, dtype=torch.int64, device=dev)
+    lc.lc_l1_mean_abs_groups(case.g, case.g.stride(0), case.gd, case.m, case.m.stride(0), W, n, HP["beta1"], end_t, cnt_t,
+                             G, mean, ws)
+    q = guarded(W, n, dev)
+    lc.lc_l1_quantize_pack_groups(case.g, case.g.stride(0), case.gd, case.m, case.m.stride(0), W, n, HP["beta1"], 1,
+                                  HP["beta2"], L, end_t, G, mean, q, q.stride(0))
+    ksum = guarded(1, n, dev)
+    lr_t = torch.tensor(lr if lr is not None else [HP["lr"]] * G, dtype=torch.float32, device=dev)
+    wd_t = torch.tensor(wd if wd is not None else [HP["wd"]] * G, dtype=torch.float32, device=dev)
+    lc.lc_level_sum_apply_groups(q, q.stride(0), W, n, L, ksum, step, tie, case.theta, end_t, lr_t, wd_t, G)
+    torch.cuda.synchronize()
+    return dict(mean=mean.cpu().numpy(), q=q, ksum=ksum)
+
+
+def check_l1_groups(case, out, L, step, ends64, counts=None, lr=None, wd=None, tie=orc.TIE_ZERO):
+    """Reference: the oracle's per-call functions applied to every segment on its own."""
+    n, W, G = case.n, case.W, len(ends64)
+    gd = orc.BF16 if case.g.dtype == torch.bfloat16 else orc.F32
+    c = np.stack([orc.local_c(case.m0[w], case.g0[w], HP["beta1"], gd) for w in range(W)])
+    fields = np.empty((W, n), np.uint8)
+    theta = case.theta0.copy()
+    for s, (lo, hi) in enumerate(segments_of(ends64, n)):
+        for w in range(W):
+            if counts is not None:
+                d = counts[s]
+                assert d <= hi - lo and not c[w, lo + d:hi].any()          # padding holds zeros
+                mean = orc.mean_abs(c[w, lo:lo + d]) if d else 0.0
+            else:
+                mean = orc.mean_abs(c[w, lo:hi]) if hi > lo else 0.0
+            assert out["mean"][w, s] == mean, "mean |c| of worker %d, group %d [%d, %d)" % (w, s, lo, hi)
+            fields[w, lo:hi] = (orc.l1_levels(c[w, lo:hi], mean, L).astype(np.int16) + L).astype(np.uint8)
+        if hi > lo:
+            K, S, u = orc.level_sum_sign(fields[:, lo:hi], L, step, tie)
+            assert np.array_equal(out["ksum"][0, lo:hi].cpu().numpy().astype(np.int32), K), "summed levels, group %d" % s
+            theta[lo:hi] = orc.apply(theta[lo:hi], u, lr[s] if lr else HP["lr"], wd[s] if wd else HP["wd"])
+    covered = segments_of(ends64, n)[-1][1]
+    assert covered == n, "the test's table must reach n"
+    assert np.array_equal(out["q"][:, :n].cpu().numpy(), fields), "level bytes"
+    assert untouched(out["q"], n) and untouched(out["ksum"], n)
+    assert_close(case.theta.cpu().numpy(), theta, "theta")
+    m_ref = np.stack([orc.momentum(case.m0[w], case.g0[w], HP["beta2"], gd) for w in range(W)])
+    assert_close(case.m.cpu().numpy(), m_ref, "momentum")
+
+
+@pytest.mark.parametrize("g_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("W,L", [(1, 127), (3, 31), (8, 15)])
+def test_l1_groups_mixed_segments(W, L, g_dtype):
+    """Segments of 64 elements up to several workgroups' worth, empty segments (repeated
+    ends), boundaries inside a 256-element tile, a ragged last segment; per-group scales
+    differ by orders of magnitude so that a wrong group shows in the levels."""
+    n = 64 * 700 + 37
+    ends64 = [1, 2, 2, 5, 9, 9, 9, 140, 141, 400, 401, 402, 530, 530, 701]
+    case = Case(n, W, seed=26000 + W, g_dtype=g_dtype, m_spread=1.0)
+    heavy_tailed(case, 11 + W, spread=2.0)
+    segs = segments_of(ends64, n)
+    for s, (lo, hi) in enumerate(segs):                                   # group s scaled by 4^(s mod 7 - 3)
+        f = 4.0 ** (s % 7 - 3)
+        case.g[:, lo:hi] = (case.g[:, lo:hi].float() * f).to(case.g.dtype)
+        case.m[:, lo:hi] *= f
+    case.snapshot()
+    G = len(ends64)
+    lr = [HP["lr"] * (1 + s) for s in range(G)]
+    wd = [0.0 if s % 2 else 0.1 for s in range(G)]
+    out = run_l1_groups(case, L, 3, ends64, lr=lr, wd=wd)
+    check_l1_groups(case, out, L, 3, ends64, lr=lr, wd=wd)
+    assert len(set(out["mean"][0].tolist())) > 8                         # the scales do differ
+
+
+def test_l1_groups_one_group_equals_flat_call():
+    n, W, L = 123457, 4, 31
+    case = Case(n, W, seed=26100)
+    heavy_tailed(case, 5, 3.0)
+    other = Case(n, W, seed=26100)
+    other.g.copy_(case.g)
+    other.snapshot()
+    flat = run_l1(other, L, 2)
+    out = run_l1_groups(case, L, 2, [(n + 63) // 64])
+    assert np.array_equal(out["mean"][:, 0], flat["mean"])
+    assert torch.equal(out["q"], flat["q"]) and torch.equal(out["ksum"], flat["ksum2"])
+    assert torch.equal(case.theta, other.theta) and torch.equal(case.m, other.m)
+
+
+def test_l1_groups_padded_tensors_use_their_true_counts():
+    """Tensors padded with zeros to multiples of 64 elements: the mean divides by the
+    tensor's own size."""
+    sizes = [768, 1000, 50, 64, 8192 * 3 + 5, 1, 0, 4099]
+    ends64, counts, off = [], [], 0
+    for sz in sizes:
+        off += (sz + 63) // 64
+        ends64.append(off)
+        counts.append(sz)
+    n = off * 64
+    W, L = 4, 31
+    case = Case(n, W, seed=26200, m_spread=1.0)
+    heavy_tailed(case, 9, 2.0)
+    for (lo, hi), sz in zip(segments_of(ends64, n), sizes):
+        case.g[:, lo + sz:hi] = 0
+        case.m[:, lo + sz:hi] = 0
+    case.snapshot()
+    out = run_l1_groups(case, L, 1, ends64, counts=counts)
+    check_l1_groups(case, out, L, 1, ends64, counts=counts)
+    assert out["mean"][0, 6] == 0.0                                       # the empty tensor
+
+
+def test_l1_groups_gpt2_small_table():
+    """The 148 tensors of GPT-2 small (Appendix F.2) scaled down 64-fold in width: many
+    short vectors between large matrices, as bench.py --groups runs at full size."""
+    tensors = synth.gpt2_tensors(96, 12, vocab=1031, n_pos=128)
+    ends64, off = [], 0
+    for _, sz in tensors:
+        off += (sz + 63) // 64
+        ends64.append(off)
+    n, W, L = off * 64, 8, 15
+    case = Case(n, W, seed=26300)
+    heavy_tailed(case, 13, 2.0)
+    for s, (lo, hi) in enumerate(segments_of(ends64, n)):
+        if hi - lo < 1024:                                                # vectors: far smaller updates
+            case.g[:, lo:hi] *= 1e-3
+            case.m[:, lo:hi] *= 1e-3
+    case.snapshot()
+    out = run_l1_groups(case, L, 2, ends64)
+    check_l1_groups(case, out, L, 2, ends64)
+
+
+def test_l1_groups_argument_checks():
+    n, W = 6400, 2
+    case = Case(n, W, seed=26400)
+    end_t = torch.tensor([50, 100], dtype=torch.int32, device="cuda")
+    mean = torch.zeros((W, 2), dtype=torch.float64, device="cuda")
+    ws = torch.zeros(lc.lc_l1_groups_workspace_words(W, 2), dtype=torch.int64, device="cuda")
+    args = (case.g, case.g.stride(0), case.gd, case.m, case.m.stride(0), W, n, 0.9)
+    assert lc.lc_l1_mean_abs_groups(*args, end_t, None, 0, mean, ws, check=False) == lc.LC_ERR_SIZE
+    assert lc.lc_l1_mean_abs_groups(*args, None, None, 2, mean, ws, check=False) == lc.LC_ERR_NULL
+    assert lc.lc_l1_mean_abs_groups(*args, end_t, None, lc.LC_MAX_GROUPS + 1, mean, ws, check=False) == lc.LC_ERR_SIZE
+    q = guarded(W, n, "cuda")
+    assert lc.lc_l1_quantize_pack_groups(*args, 1, 0.99, 15, None, 2, mean, q, q.stride(0), check=False) == lc.LC_ERR_NULL
+    assert lc.lc_l1_quantize_pack_groups(*args, 1, 0.99, 200, end_t, 2, mean, q, q.stride(0), check=False) == lc.LC_ERR_RANGE
+    assert lc.lc_l1_groups_workspace_words(0, 5) == 0 and lc.lc_l1_groups_workspace_words(2, 3) == 2 * 3 * 384 + 2
+    torch.cuda.synchronize()
+    assert torch.equal(case.m.cpu(), torch.from_numpy(case.m0))           # rejected calls touch nothing
