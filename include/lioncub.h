@@ -47,11 +47,12 @@ extern "C" {
 #endif
 
 #define LC_MAX_W 255 /* most workers one aggregation call accepts (counts fit 8 bits) */
+#define LC_MAX_GROUPS (1 << 20) /* most parameter groups a *_groups call accepts */
 
 enum {
     LC_OK = 0,
     LC_ERR_NULL = 1,  /* a required pointer is NULL                                      */
-    LC_ERR_SIZE = 2,  /* W < 1, W > LC_MAX_W, n_m out of range                           */
+    LC_ERR_SIZE = 2,  /* W < 1, W > LC_MAX_W, n_m or n_groups out of range               */
     LC_ERR_ALIGN = 3, /* a base pointer or a row stride breaks the alignment rules       */
     LC_ERR_RANGE = 4, /* p outside 1..8, or W > 2^p - 1 (the p-bit sum could overflow)   */
     LC_ERR_DTYPE = 5, /* unknown gradient dtype                                          */
@@ -155,6 +156,13 @@ int lc_pbit_sum_apply(const void *q, size_t q_stride_bytes, int in_bits, int W, 
                       size_t g_stride_elems, int g_dtype, int n_m, float beta2,
                       void *stream);
 
+/* lc_pbit_sum_apply with per-group learning rates and weight decays, group arrays as in
+ * lc_vote_apply_1bit_groups; no momentum streams. */
+int lc_pbit_sum_apply_groups(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n,
+                             int p, void *sum_out, uint64_t step, int tie_rule, float *theta,
+                             const uint32_t *group_end64, const float *group_lr,
+                             const float *group_wd, int n_groups, void *stream);
+
 /* ---- Ternary ("2-bit") wire format: exact zeros travel (Appendix B.1) ------------------
  * The worker's sign s = sign(c) in {-1, 0, +1} is sent unchanged as two 1-bit planes per
  * worker, pos (s > 0) and nz (s != 0), nothing is forced; the update is the sign of the
@@ -176,6 +184,13 @@ int lc_vote_apply_ternary(const uint64_t *pos, const uint64_t *nz, size_t q_stri
                           size_t n, float *theta, float lr, float wd, float *m,
                           size_t m_stride_elems, const void *g, size_t g_stride_elems,
                           int g_dtype, int n_m, float beta2, void *stream);
+
+/* lc_vote_apply_ternary with per-group learning rates and weight decays, group arrays as
+ * in lc_vote_apply_1bit_groups; no momentum streams. */
+int lc_vote_apply_ternary_groups(const uint64_t *pos, const uint64_t *nz, size_t q_stride_words,
+                                 int W, size_t n, float *theta, const uint32_t *group_end64,
+                                 const float *group_lr, const float *group_wd, int n_groups,
+                                 void *stream);
 
 /* ---- L1-quantised updates (Section 4.2, Equation 1 with p = 1; Appendix F.1) ---------
  * Q_1(x)_i = clamp(round(L / (2 M_1(x)) * x_i), L) with M_1(x) = mean_j |x_j| and
@@ -206,9 +221,7 @@ int lc_l1_mean_abs(const void *g, size_t g_stride_elems, int g_dtype, const floa
  * s is divided by -- the tensor's true size when the arena pads tensors with zeros up to
  * a multiple of 64; NULL divides by the segment's length.  A count or length of 0 gives
  * 0.  workspace: lc_l1_groups_workspace_words(W, n_groups) uint64 on the device,
- * overwritten.  group_end64 and group_count live on the DEVICE.  n_groups in
- * 1..LC_MAX_GROUPS, n below 2^38. */
-#define LC_MAX_GROUPS (1 << 20)
+ * overwritten.  group_end64 and group_count live on the DEVICE.  n below 2^38. */
 size_t lc_l1_groups_workspace_words(int W, int n_groups); /* host only; 0 if an argument is < 1 */
 int lc_l1_mean_abs_groups(const void *g, size_t g_stride_elems, int g_dtype, const float *m,
                           size_t m_stride_elems, int W, size_t n, float beta1,

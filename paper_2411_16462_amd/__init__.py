@@ -38,6 +38,8 @@ SIGNATURES = {
     "lc_vote_apply_1bit_groups": (_i, [_vp, _sz, _i, _sz, _u64, _i, _vp, _vp, _vp, _vp, _i, _vp]),
     "lc_pbit_sum_apply": (_i, [_vp, _sz, _i, _i, _sz, _i, _vp, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i,
                                _f, _vp]),
+    "lc_pbit_sum_apply_groups": (_i, [_vp, _sz, _i, _i, _sz, _i, _vp, _u64, _i, _vp, _vp, _vp, _vp, _i, _vp]),
+    "lc_vote_apply_ternary_groups": (_i, [_vp, _vp, _sz, _i, _sz, _vp, _vp, _vp, _vp, _i, _vp]),
     "lc_local_update_pack_ternary": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _i, _f, _vp, _vp, _sz, _vp]),
     "lc_vote_ternary": (_i, [_vp, _vp, _sz, _i, _sz, _vp, _vp, _vp]),
     "lc_vote_apply_ternary": (_i, [_vp, _vp, _sz, _i, _sz, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
@@ -178,6 +180,18 @@ def lc_vote_apply_ternary(pos, nz, q_stride_words, W, n, theta, lr, wd, m, m_str
                           n_m, beta2, stream=None, check=True):
     return _call("lc_vote_apply_ternary", check, _ptr(pos), _ptr(nz), q_stride_words, W, n, _ptr(theta), lr, wd,
                  _ptr(m), m_stride_elems, _ptr(g), g_stride_elems, g_dtype, n_m, beta2, _stream(stream))
+
+
+def lc_pbit_sum_apply_groups(q, q_stride_bytes, in_bits, W, n, p, sum_out, step, tie_rule, theta, group_end64,
+                             group_lr, group_wd, n_groups, stream=None, check=True):
+    return _call("lc_pbit_sum_apply_groups", check, _ptr(q), q_stride_bytes, in_bits, W, n, p, _ptr(sum_out), step,
+                 tie_rule, _ptr(theta), _ptr(group_end64), _ptr(group_lr), _ptr(group_wd), n_groups, _stream(stream))
+
+
+def lc_vote_apply_ternary_groups(pos, nz, q_stride_words, W, n, theta, group_end64, group_lr, group_wd, n_groups,
+                                 stream=None, check=True):
+    return _call("lc_vote_apply_ternary_groups", check, _ptr(pos), _ptr(nz), q_stride_words, W, n, _ptr(theta),
+                 _ptr(group_end64), _ptr(group_lr), _ptr(group_wd), n_groups, _stream(stream))
 
 
 def lc_l1_mean_abs(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, mean_abs, workspace, stream=None,

@@ -378,7 +378,7 @@ int lc_vote_apply_1bit_groups(const uint64_t *q, size_t q_stride_words, int W, s
                               float *theta, const uint32_t *group_end64, const float *group_lr, const float *group_wd,
                               int n_groups, void *stream)
 {
-    if (n_groups < 1) return LC_ERR_SIZE;
+    if (n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
     Groups gr;
     gr.end64 = group_end64;
     gr.lr = group_lr;
@@ -386,6 +386,35 @@ int lc_vote_apply_1bit_groups(const uint64_t *q, size_t q_stride_words, int W, s
     gr.n = n_groups;
     return aggregate(q, nullptr, q_stride_words * 8, 1, W, n, 0, 0, nullptr, nullptr, nullptr, step, tie_rule, true, theta,
                      0.0f, 0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream, gr);
+}
+
+int lc_pbit_sum_apply_groups(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n, int p, void *sum_out,
+                             uint64_t step, int tie_rule, float *theta, const uint32_t *group_end64, const float *group_lr,
+                             const float *group_wd, int n_groups, void *stream)
+{
+    if (p == 0) return LC_ERR_RANGE;
+    if (n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
+    Groups gr;
+    gr.end64 = group_end64;
+    gr.lr = group_lr;
+    gr.wd = group_wd;
+    gr.n = n_groups;
+    return aggregate(q, nullptr, q_stride_bytes, in_bits, W, n, p, 0, sum_out, nullptr, nullptr, step, tie_rule, true, theta,
+                     0.0f, 0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream, gr);
+}
+
+int lc_vote_apply_ternary_groups(const uint64_t *pos, const uint64_t *nz, size_t q_stride_words, int W, size_t n,
+                                 float *theta, const uint32_t *group_end64, const float *group_lr, const float *group_wd,
+                                 int n_groups, void *stream)
+{
+    if (n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
+    Groups gr;
+    gr.end64 = group_end64;
+    gr.lr = group_lr;
+    gr.wd = group_wd;
+    gr.n = n_groups;
+    return aggregate(pos, nz, q_stride_words * 8, 16, W, n, 0, 0, nullptr, nullptr, nullptr, 1, LC_TIE_ZERO, true, theta, 0.0f,
+                     0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream, gr);
 }
 
 int lc_container_bits(int p) { return container(p); }

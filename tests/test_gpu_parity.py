@@ -468,3 +468,53 @@ def test_groups_in_one_launch_equal_per_tensor_calls(ragged_tail):
                                         check=False) == lc.LC_ERR_NULL
     assert lc.lc_vote_apply_1bit_groups(q, q.stride(0) // 8, W, n, 2, lc.LC_TIE_ZERO, a.theta, end64, lr_t, wd_t, 0,
                                         check=False) == lc.LC_ERR_SIZE
+
+
+@pytest.mark.parametrize("kind", ["p4_fields", "p3_from_bits", "ternary"])
+def test_groups_for_field_sums_and_ternary_votes(kind):
+    """The per-group table on the other aggregation inputs: p-bit fields, 1-bit rows summed
+    as p-bit counts, and ternary planes -- one launch against the oracle applied segment by
+    segment with each segment's rate and decay."""
+    sizes = [64 * 5, 768, 64, 64 * 130, 2304, 64 * 3, 4096 * 2 + 64, 64 * 9 + 21]
+    lrs = [1e-4, 3e-3, 3e-2, 1e-4, 2e-4, 5e-5, 1e-4, 3e-3]
+    wds = [0.1, 0.0, 0.01, 0.1, 1.0, 0.1, 0.0, 0.1]
+    n, W, G = sum(sizes), 4, len(sizes)
+    case = Case(n, W, seed=17100, noise=2.0)
+    case.g[:, ::7] = 0                                                   # exact zeros: ties and zero rule at work
+    case.m[:, ::7] = 0
+    case.snapshot()
+    ends, off = [], 0
+    for sz in sizes:
+        off += sz
+        ends.append((off + 63) // 64)
+    end64 = torch.tensor(ends, dtype=torch.int32, device="cuda")
+    lr_t = torch.tensor(lrs, dtype=torch.float32, device="cuda")
+    wd_t = torch.tensor(wds, dtype=torch.float32, device="cuda")
+    nw = nwords(n)
+    step = 3
+    if kind == "ternary":
+        pos, nz = guarded(W, nw * 8, "cuda"), guarded(W, nw * 8, "cuda")
+        lc.lc_local_update_pack_ternary(case.g, case.g.stride(0), case.gd, case.m, case.m.stride(0), W, n, HP["beta1"], 0,
+                                        HP["beta2"], pos, nz, pos.stride(0) // 8)
+        lc.lc_vote_apply_ternary_groups(pos, nz, pos.stride(0) // 8, W, n, case.theta, end64, lr_t, wd_t, G)
+        u = orc.step_ternary(case.theta0, case.m0, case.g0, **HP)["u"]
+    else:
+        p, bits = (4, 4) if kind == "p4_fields" else (3, 1)
+        nbytes = (n * bits + 7) // 8
+        q = guarded(W, nbytes, "cuda")
+        lc.lc_local_update_pack(case.g, case.g.stride(0), case.gd, case.m, case.m.stride(0), W, n, HP["beta1"], 0,
+                                HP["beta2"], bits, q, q.stride(0), step, lc.LC_ZERO_ALT)
+        C = lc.lc_container_bits(p)
+        ksum = guarded(1, (n * C + 7) // 8, "cuda")
+        lc.lc_pbit_sum_apply_groups(q, q.stride(0), bits, W, n, p, ksum, step, lc.LC_TIE_ZERO, case.theta, end64, lr_t,
+                                    wd_t, G)
+        ref = orc.step_pbit(case.theta0, case.m0, case.g0, p=p, step=step, **HP)
+        u = ref["u"]
+        assert np.array_equal(ksum[0, :(n * C + 7) // 8].cpu().numpy(), ref["sum_fields"])
+    torch.cuda.synchronize()
+    want, off = np.empty(n, np.float64), 0
+    for sz, lr, wd in zip(sizes, lrs, wds):
+        want[off:off + sz] = orc.apply(case.theta0[off:off + sz], u[off:off + sz], lr, wd)
+        off += sz
+    assert (u == 0).any() and (u == 1).any() and (u == -1).any()
+    assert_close(case.theta.cpu().numpy(), want, "theta with per-group rates (%s)" % kind)
