@@ -593,6 +593,78 @@ __global__ __launch_bounds__(kVoteThreads) void vote_only_kernel(const AggParams
     if (P.vote_nz) P.vote_nz[jw] = nz & vm;
 }
 
+// Apply only (planes in): Algorithm 1 lines 5 and 6 after the allgather of the vote.  Nothing
+// is counted, so the element-per-lane layout is kept throughout and a wave is as short as in
+// the update+pack kernel: one 256-element tile of one row.  grid.y = row: row 0 also moves
+// theta, every row below n_m updates its momentum.  Lane l takes its four sign bits from
+// byte l / 2 of the tile's 32 plane bytes.  Four consecutive tiles (one 128-byte line of
+// each plane) share an XCD.
+#ifndef LC_APPLY_ONLY
+#define LC_APPLY_ONLY 1  // 0: planes-in applies go through the general kernel
+#endif
+constexpr int kApplyThreads = 64;
+
+template <int GDT, bool MOM>
+__global__ __launch_bounds__(kApplyThreads) void apply_only_kernel(const AggParams P)
+{
+    const int lane = threadIdx.x;
+    const size_t n = P.n;
+    const size_t tile = xcd_chunk_index<4>(blockIdx.x, gridDim.x) * 256;
+    if (tile >= n) return;
+    const size_t e = tile + static_cast<size_t>(lane) * 4;
+    const size_t r = blockIdx.y;
+    float *mrow = MOM ? P.m + r * P.m_stride : nullptr;
+    const void *grow = MOM ? static_cast<const char *>(P.g) + r * P.g_stride * Grad<GDT>::kBytes : nullptr;
+    const uint8_t *pos8 = reinterpret_cast<const uint8_t *>(P.in_pos);
+    const uint8_t *nz8 = reinterpret_cast<const uint8_t *>(P.in_nz);
+    const uint32_t sh = (lane & 1) * 4;
+
+    if (tile + 256 <= n) {
+        f32x4 th = {0.0f, 0.0f, 0.0f, 0.0f}, mv = th, gv = th;
+        if (r == 0) th = load4(P.theta + e);
+        if (MOM) {
+            mv = load4(mrow + e);
+            gv = Grad<GDT>::load4(grow, e);
+        }
+        if (r == 0) {
+            const uint32_t pn = static_cast<uint32_t>(pos8[e / 8]) >> sh;
+            const uint32_t zn = nz8 ? static_cast<uint32_t>(nz8[e / 8]) >> sh : 0xFu;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float uf = ((zn >> k) & 1u) ? (((pn >> k) & 1u) ? 1.0f : -1.0f) : 0.0f;
+                th[k] = __builtin_fmaf(-P.lr, __builtin_fmaf(P.wd, th[k], uf), th[k]);
+            }
+            store4(P.theta + e, th);
+        }
+        if (MOM) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) mv[k] = momentum_step(mv[k], gv[k], P.beta2, P.omb2);
+            store4(mrow + e, mv);
+        }
+        return;
+    }
+    if (e >= n) return;
+    const uint32_t pn = static_cast<uint32_t>(pos8[e / 8]) >> sh;
+    const uint32_t zn = nz8 ? static_cast<uint32_t>(nz8[e / 8]) >> sh : 0xFu;
+    for (int k = 0; k < 4 && e + k < n; ++k) {
+        if (r == 0) {
+            const float uf = ((zn >> k) & 1u) ? (((pn >> k) & 1u) ? 1.0f : -1.0f) : 0.0f;
+            const float v = P.theta[e + k];
+            P.theta[e + k] = __builtin_fmaf(-P.lr, __builtin_fmaf(P.wd, v, uf), v);
+        }
+        if (MOM) mrow[e + k] = momentum_step(mrow[e + k], Grad<GDT>::load1(grow, e + k), P.beta2, P.omb2);
+    }
+}
+
+static hipError_t launch_apply_only(const AggParams &P, int g_dtype, hipStream_t s)
+{
+    const dim3 grid(static_cast<unsigned>((P.n + 255) / 256), static_cast<unsigned>(P.n_m > 0 ? P.n_m : 1));
+    if (P.n_m == 0) apply_only_kernel<LC_F32, false><<<grid, kApplyThreads, 0, s>>>(P);
+    else if (g_dtype == LC_BF16) apply_only_kernel<LC_BF16, true><<<grid, kApplyThreads, 0, s>>>(P);
+    else apply_only_kernel<LC_F32, true><<<grid, kApplyThreads, 0, s>>>(P);
+    return hipGetLastError();
+}
+
 template <int IN, int GDT, bool APPLY, bool MOM, bool KOUT>
 static hipError_t launch_one(const AggParams &P, hipStream_t s)
 {
@@ -615,7 +687,9 @@ static hipError_t launch_in(const AggParams &P, bool apply, int g_dtype, hipStre
 hipError_t launch_aggregate(const AggParams &P, int in_kind, bool apply, bool kout, int g_dtype, hipStream_t s)
 {
     switch (in_kind) {
-    case IN_PLANES: return launch_in<IN_PLANES, false>(P, apply, g_dtype, s);
+    case IN_PLANES:
+        if (LC_APPLY_ONLY && apply && P.n_seg == 0 && !P.vote_pos && !P.vote_nz) return launch_apply_only(P, g_dtype, s);
+        return launch_in<IN_PLANES, false>(P, apply, g_dtype, s);
     case IN_BITS:
         if (!apply && !kout) {
             const size_t nw = (P.n + 63) / 64;
