@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--groups", action="store_true",
                     help="1-bit and L1 workloads with a tensor list: per-tensor learning rates (and, for L1, per-tensor "
                          "scales) through the group-table entry points, still one launch set for the arena")
+    ap.add_argument("--split", action="store_true",
+                    help="pre-packed workload (c4): lc_vote_1bit then lc_apply_update, the two calls either side of "
+                         "the allgather of the vote, instead of the fused lc_vote_apply_1bit")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (for odd and for even iterations) into HIP graphs and time replays; "
                          "per-kernel timings are then not available and the roofline entry is for the whole step")
@@ -67,7 +70,7 @@ class Kernel:
         return sum(a.elapsed_time(b) for a, b in self.events) / max(1, len(self.events))
 
 
-def build_step(wl, torch, lc, synth, per_tensor=False, groups=False):
+def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False):
     """Allocate the workload on cuda:0 and return (kernels, state) for one step."""
     dev = "cuda"
     n, W = wl.n, wl.W
@@ -81,6 +84,22 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False):
         s1 = synth.make_state(n, 1, seed=wl.seed + 1, device=dev, g_scale=1.4e-3, noise=0.0)
         theta, m, g = s1["theta"], s1["m"], s1["g"]
         st.update(q=q, theta=theta, m=m, g=g)
+        if split:
+            # the two halves as a multi-GPU run would call them around the allgather of the
+            # vote: planes out, then planes in
+            pos = torch.zeros(synth.round_up(nw, 8), dtype=torch.int64, device=dev)
+            nz = torch.zeros(synth.round_up(nw, 8), dtype=torch.int64, device=dev)
+            st.update(pos=pos, nz=nz)
+            kernels.append(Kernel(
+                "vote_1bit",
+                lambda: lc.lc_vote_1bit(q, q.stride(0), W, n, pos, nz, step_no[0], lc.LC_TIE_ZERO),
+                n * (W / 8 + 2 / 8)))
+            kernels.append(Kernel(
+                "apply_update",
+                lambda: lc.lc_apply_update(theta, pos, nz, n, hp["lr"], hp["wd"], m, m.stride(0), g, g.stride(0),
+                                           lc.LC_F32, 1, hp["beta2"]),
+                n * (2 / 8 + 8 + 8 + 4)))
+            return kernels, st, step_no
         kernels.append(Kernel(
             "vote_apply_1bit",
             lambda: lc.lc_vote_apply_1bit(q, q.stride(0), W, n, step_no[0], lc.LC_TIE_ZERO, theta, hp["lr"], hp["wd"],
@@ -337,7 +356,7 @@ def main():
     lc.load()
     torch.cuda.set_device(0)
     wl = synth.workload(args.workload)
-    kernels, st, step_no = build_step(wl, torch, lc, synth, args.per_tensor, args.groups)
+    kernels, st, step_no = build_step(wl, torch, lc, synth, args.per_tensor, args.groups, args.split)
     torch.cuda.synchronize()
     if args.copy_calibration:
         src = torch.empty(args.copy_calibration, dtype=torch.uint8, device="cuda").fill_(1)
@@ -403,7 +422,8 @@ def main():
         "config": {"workload": wl.name, "n_params": wl.n, "workers": wl.W, "mode": wl.mode, "p": wl.p,
                    "g_dtype": wl.g_dtype, "momentum_avg": wl.momentum_avg, "levels": wl.levels,
                    "calls": "per tensor" if args.per_tensor else ("one flat arena, per-tensor rates" if args.groups
-                                                                  else "one flat arena"),
+                                                                  else ("vote, then apply from planes" if args.split
+                                                                        else "one flat arena")),
                    "launch": "hip graph replay" if args.graph else "stream"},
         "step_alg_bytes": step_bytes, "step_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
