@@ -48,11 +48,12 @@ extern "C" {
 
 #define LC_MAX_W 255 /* most workers one aggregation call accepts (counts fit 8 bits) */
 #define LC_MAX_GROUPS (1 << 20) /* most parameter groups a *_groups call accepts */
+#define LC_MAX_N ((size_t)1 << 38) /* most elements per row one call accepts */
 
 enum {
     LC_OK = 0,
     LC_ERR_NULL = 1,  /* a required pointer is NULL                                      */
-    LC_ERR_SIZE = 2,  /* W < 1, W > LC_MAX_W, n_m or n_groups out of range               */
+    LC_ERR_SIZE = 2,  /* W, n_m, n_groups or n (> LC_MAX_N) out of range                 */
     LC_ERR_ALIGN = 3, /* a base pointer or a row stride breaks the alignment rules       */
     LC_ERR_RANGE = 4, /* p outside 1..8, or W > 2^p - 1 (the p-bit sum could overflow)   */
     LC_ERR_DTYPE = 5, /* unknown gradient dtype                                          */
@@ -221,7 +222,7 @@ int lc_l1_mean_abs(const void *g, size_t g_stride_elems, int g_dtype, const floa
  * s is divided by -- the tensor's true size when the arena pads tensors with zeros up to
  * a multiple of 64; NULL divides by the segment's length.  A count or length of 0 gives
  * 0.  workspace: lc_l1_groups_workspace_words(W, n_groups) uint64 on the device,
- * overwritten.  group_end64 and group_count live on the DEVICE.  n below 2^38. */
+ * overwritten.  group_end64 and group_count live on the DEVICE. */
 size_t lc_l1_groups_workspace_words(int W, int n_groups); /* host only; 0 if an argument is < 1 */
 int lc_l1_mean_abs_groups(const void *g, size_t g_stride_elems, int g_dtype, const float *m,
                           size_t m_stride_elems, int W, size_t n, float beta1,

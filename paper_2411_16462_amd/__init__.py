@@ -20,6 +20,7 @@ LC_TIE_ZERO, LC_TIE_ALT = 0, 1
 LC_MAX_W = 255
 LC_L1_WORKSPACE_WORDS = 384
 LC_MAX_GROUPS = 1 << 20
+LC_MAX_N = 1 << 38
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblioncub.so")
 

@@ -46,7 +46,7 @@ int aggregate(const void *q, const void *q2, size_t q_stride_bytes, int in_bits,
               size_t m_stride, const void *g, size_t g_stride, int g_dtype, int n_m, float beta2, void *stream,
               const Groups &groups = Groups())
 {
-    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N) return LC_ERR_SIZE;
     if (groups.n < 0 || (groups.n > 0 && (!groups.end64 || !groups.lr || !groups.wd))) return groups.n < 0 ? LC_ERR_SIZE : LC_ERR_NULL;
     if (tie_rule != LC_TIE_ZERO && tie_rule != LC_TIE_ALT) return LC_ERR_MODE;
     int sum_bits = 0;
@@ -123,7 +123,7 @@ int lc_local_update_pack(const void *g, size_t g_stride_elems, int g_dtype, floa
                          size_t n, float beta1, int update_m, float beta2, int out_bits, void *q, size_t q_stride_bytes,
                          uint64_t step, int zero_rule, void *stream)
 {
-    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N) return LC_ERR_SIZE;
     if (out_bits != 1 && out_bits != 2 && out_bits != 4 && out_bits != 8) return LC_ERR_MODE;
     if (zero_rule != LC_ZERO_ALT && zero_rule != LC_ZERO_POS && zero_rule != LC_ZERO_NEG) return LC_ERR_MODE;
     if (!q && !update_m) return LC_ERR_NULL;
@@ -177,7 +177,7 @@ int lc_apply_update(float *theta, const uint64_t *vote_pos, const uint64_t *vote
 {
     if (!theta || !vote_pos) return LC_ERR_NULL;
     if (!aligned(theta, 16) || !aligned(vote_pos, 8) || !aligned(vote_nz, 8)) return LC_ERR_ALIGN;
-    if (n_m < 0 || n_m > LC_MAX_W) return LC_ERR_SIZE;
+    if (n_m < 0 || n_m > LC_MAX_W || n > LC_MAX_N) return LC_ERR_SIZE;
     if (n_m > 0) {
         const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, n_m);
         if (rc) return rc;
@@ -206,7 +206,7 @@ int lc_apply_update(float *theta, const uint64_t *vote_pos, const uint64_t *vote
 
 int lc_momentum_avg(float *m, size_t m_stride_elems, int W, size_t n, void *stream)
 {
-    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N) return LC_ERR_SIZE;
     if (!m) return LC_ERR_NULL;
     if (!aligned(m, 16) || (W > 1 && (m_stride_elems * 4) % 16 != 0)) return LC_ERR_ALIGN;
     if (n == 0 || W == 1) return LC_OK;
@@ -216,7 +216,7 @@ int lc_momentum_avg(float *m, size_t m_stride_elems, int W, size_t n, void *stre
 int lc_l1_mean_abs(const void *g, size_t g_stride_elems, int g_dtype, const float *m, size_t m_stride_elems, int W, size_t n,
                    float beta1, double *mean_abs, uint64_t *workspace, void *stream)
 {
-    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N) return LC_ERR_SIZE;
     const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
     if (rc) return rc;
     if (!mean_abs || !workspace) return LC_ERR_NULL;
@@ -236,8 +236,7 @@ int lc_l1_mean_abs_groups(const void *g, size_t g_stride_elems, int g_dtype, con
                           size_t n, float beta1, const uint32_t *group_end64, const uint64_t *group_count, int n_groups,
                           double *mean_abs, uint64_t *workspace, void *stream)
 {
-    if (W < 1 || W > LC_MAX_W || n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
-    if ((n + 63) / 64 > 0xFFFFFFFFull) return LC_ERR_SIZE;
+    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N || n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
     const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
     if (rc) return rc;
     if (!mean_abs || !workspace || !group_end64) return LC_ERR_NULL;
@@ -255,7 +254,7 @@ int lc_l1_quantize_pack(const void *g, size_t g_stride_elems, int g_dtype, float
                         float beta1, int update_m, float beta2, int levels, const double *mean_abs, uint8_t *q,
                         size_t q_stride_bytes, void *stream)
 {
-    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N) return LC_ERR_SIZE;
     if (levels < 1 || levels > 127) return LC_ERR_RANGE;
     const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
     if (rc) return rc;
@@ -270,8 +269,7 @@ int lc_l1_quantize_pack_groups(const void *g, size_t g_stride_elems, int g_dtype
                                size_t n, float beta1, int update_m, float beta2, int levels, const uint32_t *group_end64,
                                int n_groups, const double *mean_abs, uint8_t *q, size_t q_stride_bytes, void *stream)
 {
-    if (W < 1 || W > LC_MAX_W || n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
-    if ((n + 63) / 64 > 0xFFFFFFFFull) return LC_ERR_SIZE;
+    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N || n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
     if (levels < 1 || levels > 127) return LC_ERR_RANGE;
     const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
     if (rc) return rc;
@@ -322,7 +320,7 @@ int lc_local_update_pack_ternary(const void *g, size_t g_stride_elems, int g_dty
                                  size_t n, float beta1, int update_m, float beta2, uint64_t *pos, uint64_t *nz,
                                  size_t q_stride_words, void *stream)
 {
-    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N) return LC_ERR_SIZE;
     const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
     if (rc) return rc;
     if (!pos || !nz) return LC_ERR_NULL;
@@ -350,7 +348,7 @@ int lc_vote_apply_ternary(const uint64_t *pos, const uint64_t *nz, size_t q_stri
 
 int lc_momentum_divergence(const float *m, size_t m_stride_elems, int W, size_t n, double *max_std, void *stream)
 {
-    if (W < 1 || W > LC_MAX_W) return LC_ERR_SIZE;
+    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N) return LC_ERR_SIZE;
     if (!m || !max_std) return LC_ERR_NULL;
     if (!aligned(m, 16) || (W > 1 && (m_stride_elems * 4) % 16 != 0) || !aligned(max_std, 8)) return LC_ERR_ALIGN;
     return from_hip(launch_momentum_divergence(m, m_stride_elems, W, n, max_std, static_cast<hipStream_t>(stream)));
@@ -363,8 +361,10 @@ int lc_momentum_sync_ranges(float *m, size_t m_stride_elems, int W, const size_t
     if (every == 0) return LC_ERR_MODE;
     if (!m || (n_ranges > 0 && (!offsets || !sizes))) return LC_ERR_NULL;
     if (!aligned(m, 16) || (W > 1 && (m_stride_elems * 4) % 16 != 0)) return LC_ERR_ALIGN;
-    for (int r = 0; r < n_ranges; ++r)
+    for (int r = 0; r < n_ranges; ++r) {
         if (offsets[r] % 4 != 0) return LC_ERR_ALIGN;
+        if (sizes[r] > LC_MAX_N) return LC_ERR_SIZE;
+    }
     if (step % every != 0 || W == 1) return LC_OK;  // not a synchronisation step
     for (int r = 0; r < n_ranges; ++r) {
         if (sizes[r] == 0) continue;
@@ -424,7 +424,7 @@ const char *lc_status_string(int status)
     switch (status) {
     case LC_OK: return "LC_OK";
     case LC_ERR_NULL: return "LC_ERR_NULL: a required pointer is NULL";
-    case LC_ERR_SIZE: return "LC_ERR_SIZE: worker count out of range";
+    case LC_ERR_SIZE: return "LC_ERR_SIZE: worker, row, group or element count out of range";
     case LC_ERR_ALIGN: return "LC_ERR_ALIGN: pointer or row stride misaligned";
     case LC_ERR_RANGE: return "LC_ERR_RANGE: p outside 1..8 or W > 2^p - 1";
     case LC_ERR_DTYPE: return "LC_ERR_DTYPE: unknown gradient dtype";

@@ -205,3 +205,41 @@ def test_divergence_and_sync_ranges_validation():
     assert lc.lc_momentum_sync_ranges(**{**s, "m": None}) == lc.LC_ERR_NULL
     assert lc.lc_momentum_sync_ranges(**{**s, "n_ranges": 0, "step": 10}) == lc.LC_OK
     assert lc.lc_momentum_sync_ranges(**{**s, "sizes": [0, 0], "step": 10}) == lc.LC_OK   # empty ranges: no launch
+
+
+def test_element_and_group_count_limits():
+    """n beyond LC_MAX_N and group counts outside 1..LC_MAX_GROUPS are refused before any
+    launch, by every entry point that takes them."""
+    text = open(HEADER).read()
+    assert "#define LC_MAX_N ((size_t)1 << 38)" in text and lc.LC_MAX_N == 1 << 38
+    assert "#define LC_MAX_GROUPS (1 << 20)" in text and lc.LC_MAX_GROUPS == 1 << 20
+    big = lc.LC_MAX_N + 1
+    assert pack(n=big) == lc.LC_ERR_SIZE
+    assert lc.lc_vote_1bit(A, 16, 4, big, A, A, 1, lc.LC_TIE_ZERO, stream=0, check=False) == lc.LC_ERR_SIZE
+    assert lc.lc_pbit_sum_sign(A, 512, 4, 8, big, 4, A, None, None, 1, lc.LC_TIE_ZERO, stream=0, check=False) == lc.LC_ERR_SIZE
+    assert lc.lc_apply_update(A, A, A, big, 1e-4, 0.1, None, 0, None, 0, lc.LC_F32, 0, 0.99, stream=0,
+                              check=False) == lc.LC_ERR_SIZE
+    assert lc.lc_momentum_avg(A, 1024, 4, big, stream=0, check=False) == lc.LC_ERR_SIZE
+    assert lc.lc_momentum_divergence(A, 1024, 4, big, A, stream=0, check=False) == lc.LC_ERR_SIZE
+    assert lc.lc_l1_mean_abs(A, 1024, lc.LC_F32, A, 1024, 4, big, 0.9, A, A, stream=0, check=False) == lc.LC_ERR_SIZE
+    assert lc.lc_l1_quantize_pack(A, 1024, lc.LC_F32, A, 1024, 4, big, 0.9, 1, 0.99, 15, A, A, 1024, stream=0,
+                                  check=False) == lc.LC_ERR_SIZE
+    assert lc.lc_local_update_pack_ternary(A, 1024, lc.LC_F32, A, 1024, 4, big, 0.9, 1, 0.99, A, A, 16, stream=0,
+                                           check=False) == lc.LC_ERR_SIZE
+    for G in (0, -3, lc.LC_MAX_GROUPS + 1):
+        assert lc.lc_vote_apply_1bit_groups(A, 16, 4, 0, 1, lc.LC_TIE_ZERO, A, A, A, A, G, stream=0,
+                                            check=False) == lc.LC_ERR_SIZE
+        assert lc.lc_pbit_sum_apply_groups(A, 512, 4, 8, 0, 4, None, 1, lc.LC_TIE_ZERO, A, A, A, A, G, stream=0,
+                                           check=False) == lc.LC_ERR_SIZE
+        assert lc.lc_vote_apply_ternary_groups(A, A, 16, 4, 0, A, A, A, A, G, stream=0, check=False) == lc.LC_ERR_SIZE
+        assert lc.lc_level_sum_apply_groups(A, 1024, 4, 0, 15, None, 1, lc.LC_TIE_ZERO, A, A, A, A, G, stream=0,
+                                            check=False) == lc.LC_ERR_SIZE
+        assert lc.lc_l1_mean_abs_groups(A, 1024, lc.LC_F32, A, 1024, 4, 0, 0.9, A, None, G, A, A, stream=0,
+                                        check=False) == lc.LC_ERR_SIZE
+        assert lc.lc_l1_quantize_pack_groups(A, 1024, lc.LC_F32, A, 1024, 4, 0, 0.9, 1, 0.99, 15, A, G, A, A, 1024,
+                                             stream=0, check=False) == lc.LC_ERR_SIZE
+    # a valid table with n = 0 is a no-op
+    assert lc.lc_vote_apply_1bit_groups(A, 16, 4, 0, 1, lc.LC_TIE_ZERO, A, A, A, A, 3, stream=0, check=False) == lc.LC_OK
+    assert lc.lc_l1_quantize_pack_groups(A, 1024, lc.LC_F32, A, 1024, 4, 0, 0.9, 1, 0.99, 15, A, 3, A, A, 1024, stream=0,
+                                         check=False) == lc.LC_OK
+    assert lc.lc_l1_groups_workspace_words(8, 148) == 8 * 148 * lc.LC_L1_WORKSPACE_WORDS + 75
