@@ -121,6 +121,13 @@ int lc_momentum_avg(float *m, size_t m_stride_elems, int W, size_t n, void *stre
 int lc_momentum_divergence(const float *m, size_t m_stride_elems, int W, size_t n,
                            double *max_std, void *stream);
 
+/* The same quantity for every parameter group in one launch (Figure 6 plots it per layer):
+ * max_std[s] (n_groups doubles on the device) is the maximum over segment s of the group
+ * table (as in lc_vote_apply_1bit_groups; device array); an empty segment gives 0. */
+int lc_momentum_divergence_groups(const float *m, size_t m_stride_elems, int W, size_t n,
+                                  const uint32_t *group_end64, int n_groups, double *max_std,
+                                  void *stream);
+
 /* Section 5 / 6.2, the policy the paper recommends: synchronise the momenta of selected
  * layers only, every `every` iterations (e.g. head and embedding, every 10).  If step is a
  * multiple of `every`, runs lc_momentum_avg on each range [offsets[r], offsets[r] +

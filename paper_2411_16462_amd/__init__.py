@@ -34,6 +34,7 @@ SIGNATURES = {
     "lc_apply_update": (_i, [_vp, _vp, _vp, _sz, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
     "lc_momentum_avg": (_i, [_vp, _sz, _i, _sz, _vp]),
     "lc_momentum_divergence": (_i, [_vp, _sz, _i, _sz, _vp, _vp]),
+    "lc_momentum_divergence_groups": (_i, [_vp, _sz, _i, _sz, _vp, _i, _vp, _vp]),
     "lc_momentum_sync_ranges": (_i, [_vp, _sz, _i, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), _i, _u64, _u64, _vp]),
     "lc_vote_apply_1bit": (_i, [_vp, _sz, _i, _sz, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
     "lc_vote_apply_1bit_groups": (_i, [_vp, _sz, _i, _sz, _u64, _i, _vp, _vp, _vp, _vp, _i, _vp]),
@@ -137,6 +138,11 @@ def lc_momentum_avg(m, m_stride_elems, W, n, stream=None, check=True):
 
 def lc_momentum_divergence(m, m_stride_elems, W, n, max_std, stream=None, check=True):
     return _call("lc_momentum_divergence", check, _ptr(m), m_stride_elems, W, n, _ptr(max_std), _stream(stream))
+
+
+def lc_momentum_divergence_groups(m, m_stride_elems, W, n, group_end64, n_groups, max_std, stream=None, check=True):
+    return _call("lc_momentum_divergence_groups", check, _ptr(m), m_stride_elems, W, n, _ptr(group_end64), n_groups,
+                 _ptr(max_std), _stream(stream))
 
 
 def lc_momentum_sync_ranges(m, m_stride_elems, W, offsets, sizes, n_ranges, step, every, stream=None, check=True):

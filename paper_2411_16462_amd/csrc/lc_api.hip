@@ -351,7 +351,18 @@ int lc_momentum_divergence(const float *m, size_t m_stride_elems, int W, size_t 
     if (W < 1 || W > LC_MAX_W || n > LC_MAX_N) return LC_ERR_SIZE;
     if (!m || !max_std) return LC_ERR_NULL;
     if (!aligned(m, 16) || (W > 1 && (m_stride_elems * 4) % 16 != 0) || !aligned(max_std, 8)) return LC_ERR_ALIGN;
-    return from_hip(launch_momentum_divergence(m, m_stride_elems, W, n, max_std, static_cast<hipStream_t>(stream)));
+    return from_hip(launch_momentum_divergence(m, m_stride_elems, W, n, max_std, nullptr, 0, static_cast<hipStream_t>(stream)));
+}
+
+int lc_momentum_divergence_groups(const float *m, size_t m_stride_elems, int W, size_t n, const uint32_t *group_end64,
+                                  int n_groups, double *max_std, void *stream)
+{
+    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N || n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
+    if (!m || !max_std || !group_end64) return LC_ERR_NULL;
+    if (!aligned(m, 16) || (W > 1 && (m_stride_elems * 4) % 16 != 0) || !aligned(max_std, 8) || !aligned(group_end64, 4))
+        return LC_ERR_ALIGN;
+    return from_hip(launch_momentum_divergence(m, m_stride_elems, W, n, max_std, group_end64, n_groups,
+                                               static_cast<hipStream_t>(stream)));
 }
 
 int lc_momentum_sync_ranges(float *m, size_t m_stride_elems, int W, const size_t *offsets, const size_t *sizes, int n_ranges,

@@ -43,7 +43,9 @@ hipError_t launch_local_update_pack(const void *g, size_t g_stride, int g_dtype,
 // kout: the counts K are wanted as fields from 1-bit rows.
 hipError_t launch_aggregate(const AggParams &P, int in_kind, bool apply, bool kout, int g_dtype, hipStream_t s);
 hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStream_t s);
-hipError_t launch_momentum_divergence(const float *m, size_t stride, int W, size_t n, double *out, hipStream_t s);
+// n_groups = 0: one maximum over the whole range; else one per segment of the group table
+hipError_t launch_momentum_divergence(const float *m, size_t stride, int W, size_t n, double *out, const uint32_t *end64,
+                                      int n_groups, hipStream_t s);
 hipError_t launch_local_update_pack_ternary(const void *g, size_t g_stride, int g_dtype, float *m, size_t m_stride, int W,
                                             size_t n, float beta1, bool update_m, float beta2, uint64_t *pos, uint64_t *nz,
                                             size_t stride_words, hipStream_t s);

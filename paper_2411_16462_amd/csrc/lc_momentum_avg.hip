@@ -80,10 +80,45 @@ hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStre
 // max over elements of the standard deviation across the W workers (divisor W), in fp64
 // with the workers taken in order, so that the result equals a sequential evaluation bit
 // for bit; the maximum is order-free.  Reads W * 4 bytes per element, writes one double.
-__global__ void divergence_zero_kernel(double *out) { *out = 0.0; }
+__global__ void divergence_zero_kernel(double *out, int count)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) out[i] = 0.0;
+}
 
+// non-negative doubles order like their bit patterns
+__device__ __forceinline__ unsigned long long wave_max_bits(unsigned long long bits, int lane)
+{
+#pragma unroll
+    for (int mask = 1; mask < kWave; mask <<= 1) {
+        const int addr = (lane ^ mask) << 2;
+        const unsigned lo = static_cast<unsigned>(__builtin_amdgcn_ds_bpermute(addr, static_cast<int>(bits & 0xFFFFFFFFull)));
+        const unsigned hi = static_cast<unsigned>(__builtin_amdgcn_ds_bpermute(addr, static_cast<int>(bits >> 32)));
+        const unsigned long long o = (static_cast<unsigned long long>(hi) << 32) | lo;
+        bits = o > bits ? o : bits;
+    }
+    return bits;
+}
+
+// Raise *dst to the standard deviation that belongs to the sum of squares `ss`.  The plain
+// read first spares the atomic once the running maximum has passed this value (a stale
+// read can only cause a superfluous atomic, never a lost one: the value only grows).
+__device__ __forceinline__ void publish_std(double *dst, double ss, int W)
+{
+    if (!(ss > 0.0)) return;
+    const double sd = sqrt(ss / static_cast<double>(W));
+    const unsigned long long bits = static_cast<unsigned long long>(__double_as_longlong(sd));
+    unsigned long long *p = reinterpret_cast<unsigned long long *>(dst);
+    if (bits > *reinterpret_cast<volatile unsigned long long *>(p)) atomicMax(p, bits);
+}
+
+// GROUPED: out[s] receives the maximum over segment s of a group table (segment ends in
+// units of 64 elements).  A wave whose 256 elements lie in one segment reduces first; a wave
+// that straddles a boundary lets every lane publish its own value.
+template <bool GROUPED>
 __global__ __launch_bounds__(256) void momentum_divergence_kernel(const float *__restrict__ m, size_t stride, int W, size_t n,
-                                                                  double *__restrict__ out)
+                                                                  double *__restrict__ out,
+                                                                  const uint32_t *__restrict__ end64, int G)
 {
     __shared__ double s_max[4];
     const int lane = threadIdx.x & (kWave - 1);
@@ -112,34 +147,53 @@ __global__ __launch_bounds__(256) void momentum_divergence_kernel(const float *_
         for (int k = 0; k < 4; ++k)
             if (e + k < n && ss[k] > worst) worst = ss[k];
     }
-    // non-negative doubles order like their bit patterns
     unsigned long long bits = static_cast<unsigned long long>(__double_as_longlong(worst));
-#pragma unroll
-    for (int mask = 1; mask < kWave; mask <<= 1) {
-        const int addr = (lane ^ mask) << 2;
-        const unsigned lo = static_cast<unsigned>(__builtin_amdgcn_ds_bpermute(addr, static_cast<int>(bits & 0xFFFFFFFFull)));
-        const unsigned hi = static_cast<unsigned>(__builtin_amdgcn_ds_bpermute(addr, static_cast<int>(bits >> 32)));
-        const unsigned long long o = (static_cast<unsigned long long>(hi) << 32) | lo;
-        bits = o > bits ? o : bits;
+    if (GROUPED) {
+        // segment of the wave's first 64-element block by bisection (uniform), then each
+        // lane walks on to the segment of its own block; lanes past n stay with the last
+        const size_t first = (static_cast<size_t>(blockIdx.x) * 256 + static_cast<size_t>(wave) * kWave) * 4;
+        const uint32_t t64 = static_cast<uint32_t>(first / 64);
+        int lo = 0, hi = G - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (end64[mid] > t64) hi = mid;
+            else lo = mid + 1;
+        }
+        int seg = lo;
+        if (e < n) {
+            const uint32_t e64 = static_cast<uint32_t>(e / 64);
+            while (seg < G - 1 && e64 >= end64[seg]) ++seg;
+        } else {
+            seg = G - 1;
+        }
+        const int seg0 = __builtin_amdgcn_readfirstlane(seg);
+        if (__ballot(seg != seg0) == 0) {
+            bits = wave_max_bits(bits, lane);
+            if (lane == 0) publish_std(out + seg0, __longlong_as_double(static_cast<long long>(bits)), W);
+        } else {
+            publish_std(out + seg, worst, W);
+        }
+        return;
     }
+    bits = wave_max_bits(bits, lane);
     if (lane == 0) s_max[wave] = __longlong_as_double(static_cast<long long>(bits));
     __syncthreads();
     if (threadIdx.x == 0) {
         double b = s_max[0];
         for (int r = 1; r < 4; ++r) b = s_max[r] > b ? s_max[r] : b;
-        if (b > 0.0) {
-            const double sd = sqrt(b / static_cast<double>(W));
-            atomicMax(reinterpret_cast<unsigned long long *>(out), static_cast<unsigned long long>(__double_as_longlong(sd)));
-        }
+        publish_std(out, b, W);
     }
 }
 
-hipError_t launch_momentum_divergence(const float *m, size_t stride, int W, size_t n, double *out, hipStream_t s)
+hipError_t launch_momentum_divergence(const float *m, size_t stride, int W, size_t n, double *out, const uint32_t *end64,
+                                      int n_groups, hipStream_t s)
 {
-    divergence_zero_kernel<<<1, 1, 0, s>>>(out);
+    const int count = n_groups > 0 ? n_groups : 1;
+    divergence_zero_kernel<<<(count + 255) / 256, 256, 0, s>>>(out, count);
     if (n > 0) {
         const unsigned grid = static_cast<unsigned>((n + 1023) / 1024);
-        momentum_divergence_kernel<<<grid, 256, 0, s>>>(m, stride, W, n, out);
+        if (n_groups > 0) momentum_divergence_kernel<true><<<grid, 256, 0, s>>>(m, stride, W, n, out, end64, n_groups);
+        else momentum_divergence_kernel<false><<<grid, 256, 0, s>>>(m, stride, W, n, out, nullptr, 0);
     }
     return hipGetLastError();
 }

@@ -358,6 +358,36 @@ def test_momentum_divergence(W, n):
     assert float(out[0]) == 0.0
 
 
+@pytest.mark.parametrize("W", [2, 5, 16])
+def test_momentum_divergence_per_group(W):
+    """The same metric for every segment of a group table in one launch (Figure 6 is per
+    layer): each value against the oracle run on that segment alone.  Segments of 64
+    elements, boundaries inside a wave's 256 elements, empty segments, a ragged end; the
+    spread differs per segment so that a value landing in the wrong slot shows."""
+    ends64 = [1, 2, 2, 7, 40, 41, 41, 300, 1000, 1003]
+    n = 64 * 1003 - 29
+    case = Case(n, W, seed=14500 + W, m_spread=0.3)
+    G = len(ends64)
+    bounds = [0] + [min(e * 64, n) for e in ends64]
+    for s in range(G):
+        case.m[:, bounds[s]:bounds[s + 1]] *= 2.0 ** (s % 5)
+    case.snapshot()
+    end_t = torch.tensor(ends64, dtype=torch.int32, device="cuda")
+    out = torch.full((G,), -1.0, dtype=torch.float64, device="cuda")
+    lc.lc_momentum_divergence_groups(case.m, case.m.stride(0), W, n, end_t, G, out)
+    whole = torch.full((1,), -1.0, dtype=torch.float64, device="cuda")
+    lc.lc_momentum_divergence(case.m, case.m.stride(0), W, n, whole)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    for s in range(G):
+        lo, hi = bounds[s], bounds[s + 1]
+        ref = orc.momentum_divergence(case.m0[:, lo:hi]) if hi > lo else 0.0
+        assert abs(got[s] - ref) <= 1e-12 * ref, "segment %d [%d, %d): %r vs %r" % (s, lo, hi, got[s], ref)
+    assert got.max() == float(whole[0]) and len(set(got.tolist())) >= 7
+    assert lc.lc_momentum_divergence_groups(case.m, case.m.stride(0), W, n, None, G, out, check=False) == lc.LC_ERR_NULL
+    assert lc.lc_momentum_divergence_groups(case.m, case.m.stride(0), W, n, end_t, 0, out, check=False) == lc.LC_ERR_SIZE
+
+
 def test_momentum_sync_ranges_policy():
     """Selected ranges only, and only on every k-th iteration (Section 6.2: head and
     embedding every ten iterations)."""
