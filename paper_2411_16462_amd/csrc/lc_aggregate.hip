@@ -665,6 +665,176 @@ static hipError_t launch_apply_only(const AggParams &P, int g_dtype, hipStream_t
     return hipGetLastError();
 }
 
+// Aggregate + apply for few workers, one 256-element tile per wave (no momentum streams).
+// With W small the packed rows are a small part of the traffic (W/8 .. W bytes per element
+// against 8 for theta), so the kernel takes the shape that streams theta fastest -- the
+// update+pack kernel's: lane l owns elements 4l..4l+3, a wave lives for one tile -- and each
+// lane counts its own four elements in four byte-wide counters of one register:
+//   1-bit rows   one byte load per row and lane (lanes 2k, 2k+1 share it), the lane's nibble
+//                spread to bit 0 of each counter byte (multiply by 2^0 + 2^7 + 2^14 + 2^21);
+//   ternary      the same for pos & nz and for nz & ~pos;
+//   field rows   the lane's 1 / 2 / 4 bytes of fields are added as integers (no carry
+//                crosses a field), then spread to bytes.
+// About W vector instructions per element: fine up to W = 32 (a budget of about 50 at
+// 8 TB/s); beyond that the bit-sliced kernel above takes over.
+constexpr int kTileThreads = 64;
+#ifndef LC_TILE_MAX_W_BITS
+#define LC_TILE_MAX_W_BITS 32  // 1-bit and ternary rows: largest W served by the tile kernel (0 disables it)
+#endif
+#ifndef LC_TILE_FIELDS
+#define LC_TILE_FIELDS 1       // field rows through the tile kernel
+#endif
+
+__device__ __forceinline__ uint32_t nibble_to_bytes(uint32_t nib) { return (nib * 0x00204081u) & 0x01010101u; }
+
+template <int IN, bool KOUT, bool GROUPED>
+__global__ __launch_bounds__(kTileThreads) void tile_apply_kernel(const AggParams P)
+{
+    const int lane = threadIdx.x;
+    const size_t n = P.n;
+    const size_t tile = xcd_chunk_index<4>(blockIdx.x, gridDim.x) * 256;
+    if (tile >= n) return;
+    const size_t e = tile + static_cast<size_t>(lane) * 4;
+    if (e >= n) return;
+    const int left = n - e >= 4 ? 4 : static_cast<int>(n - e);
+    const bool full = left == 4;
+    const int W = P.W;
+    const size_t stride = P.q_stride_bytes;
+    const uint8_t *q8 = static_cast<const uint8_t *>(P.q);
+    const uint8_t *z8 = static_cast<const uint8_t *>(P.q2);
+    const uint32_t sh = (lane & 1) * 4;
+
+    f32x4 th = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (full) th = load4(P.theta + e);
+    else for (int k = 0; k < left; ++k) th[k] = P.theta[e + k];
+
+    // counts: byte k of kp = K (or K+) of element e + k, byte k of kn = K- (ternary only)
+    uint32_t kp = 0, kn = 0;
+    if constexpr (IN == IN_BITS || IN == IN_TERNARY) {
+        // every byte that holds a bit of an element below n lies inside the row
+        const size_t off = e / 8;
+        int w = 0;
+        for (; w + 8 <= W; w += 8) {
+            uint32_t x[8], z[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                x[i] = q8[static_cast<size_t>(w + i) * stride + off];
+                if (IN == IN_TERNARY) z[i] = z8[static_cast<size_t>(w + i) * stride + off];
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (IN == IN_TERNARY) {
+                    kp += nibble_to_bytes(((x[i] & z[i]) >> sh) & 0xFu);
+                    kn += nibble_to_bytes(((z[i] & ~x[i]) >> sh) & 0xFu);
+                } else {
+                    kp += nibble_to_bytes((x[i] >> sh) & 0xFu);
+                }
+            }
+        }
+        for (; w < W; ++w) {
+            const uint32_t x = q8[static_cast<size_t>(w) * stride + off];
+            if (IN == IN_TERNARY) {
+                const uint32_t z = z8[static_cast<size_t>(w) * stride + off];
+                kp += nibble_to_bytes(((x & z) >> sh) & 0xFu);
+                kn += nibble_to_bytes(((z & ~x) >> sh) & 0xFu);
+            } else {
+                kp += nibble_to_bytes((x >> sh) & 0xFu);
+            }
+        }
+    } else {
+        // IN-bit fields: the lane's four fields are IN / 2 bytes at byte e * IN / 8; in a
+        // ragged lane only the bytes that hold elements below n are read
+        const size_t off = e * IN / 8;
+        const int bytes = full ? IN / 2 : (left * IN + 7) / 8;
+        uint32_t acc = 0;
+        int w = 0;
+        if (full) {
+            for (; w + 8 <= W; w += 8) {
+                uint32_t x[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uint8_t *src = q8 + static_cast<size_t>(w + i) * stride + off;
+                    if (IN == 8) x[i] = *reinterpret_cast<const uint32_t *>(src);
+                    else if (IN == 4) x[i] = *reinterpret_cast<const uint16_t *>(src);
+                    else x[i] = *src;
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc += x[i];
+            }
+        }
+        for (; w < W; ++w) {
+            const uint8_t *src = q8 + static_cast<size_t>(w) * stride + off;
+            uint32_t x = 0;
+            for (int b = 0; b < bytes; ++b) x |= static_cast<uint32_t>(src[b]) << (8 * b);
+            acc += x;
+        }
+        if (!full) acc &= (1u << (left * IN)) - 1u;  // fields of elements at and beyond n do not count
+        if (IN == 8) kp = acc;
+        else if (IN == 4) kp = (acc & 0xFu) | ((acc & 0xF0u) << 4) | ((acc & 0xF00u) << 8) | ((acc & 0xF000u) << 12);
+        else kp = (acc & 0x3u) | ((acc & 0xCu) << 6) | ((acc & 0x30u) << 12) | ((acc & 0xC0u) << 18);
+        if (P.sum_out) {  // the summed fields, in the rows' own format
+            uint8_t *dst = static_cast<uint8_t *>(P.sum_out) + off;
+            if (full && IN == 8) *reinterpret_cast<uint32_t *>(dst) = acc;
+            else if (full && IN == 4) *reinterpret_cast<uint16_t *>(dst) = static_cast<uint16_t>(acc);
+            else for (int b = 0; b < bytes; ++b) dst[b] = static_cast<uint8_t>(acc >> (8 * b));
+        }
+    }
+    if constexpr (KOUT) {  // counts from 1-bit rows as C-bit fields, C = 2, 4 or 8
+        const int C = P.sum_bits;
+        uint8_t *out = static_cast<uint8_t *>(P.sum_out);
+        const uint32_t valid = left == 4 ? 0xFFFFFFFFu : ((1u << (8 * left)) - 1u);
+        const uint32_t kb = kp & valid;
+        if (C == 8) {
+            if (full) *reinterpret_cast<uint32_t *>(out + e) = kb;
+            else for (int k = 0; k < left; ++k) out[e + k] = static_cast<uint8_t>(kb >> (8 * k));
+        } else if (C == 4) {
+            const uint32_t v = (kb & 0xFu) | ((kb >> 4) & 0xF0u) | ((kb >> 8) & 0xF00u) | ((kb >> 12) & 0xF000u);
+            if (left > 2) *reinterpret_cast<uint16_t *>(out + e / 2) = static_cast<uint16_t>(v);
+            else out[e / 2] = static_cast<uint8_t>(v);
+        } else {
+            const uint32_t v = (kb & 0x3u) | ((kb >> 6) & 0xCu) | ((kb >> 12) & 0x30u) | ((kb >> 18) & 0xC0u);
+            out[e / 4] = static_cast<uint8_t>(v);
+        }
+    }
+
+    float lr = P.lr, wd = P.wd;
+    if (GROUPED) {
+        // first group that ends beyond the tile's first 64-element block (uniform), then
+        // each lane walks on to the group of its own block
+        const uint32_t t64 = static_cast<uint32_t>(tile / 64);
+        int lo = 0, hi = P.n_seg - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (P.seg_end64[mid] > t64) hi = mid;
+            else lo = mid + 1;
+        }
+        const uint32_t e64 = static_cast<uint32_t>(e / 64);
+        while (lo < P.n_seg - 1 && e64 >= P.seg_end64[lo]) ++lo;
+        lr = P.seg_lr[lo];
+        wd = P.seg_wd[lo];
+    }
+    // u per element: K against the threshold (or K+ against K-); what a tie gives is uniform
+    const float tie_u = (IN == IN_TERNARY) ? 0.0f : (!P.tie_possible ? -1.0f : (P.tie < 0 ? 0.0f : (P.tie > 0 ? 1.0f : -1.0f)));
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int a = static_cast<int>((kp >> (8 * k)) & 0xFFu);
+        const int b = (IN == IN_TERNARY) ? static_cast<int>((kn >> (8 * k)) & 0xFFu) : P.thresh;
+        const float uf = a > b ? 1.0f : (a == b ? tie_u : -1.0f);
+        th[k] = __builtin_fmaf(-lr, __builtin_fmaf(wd, th[k], uf), th[k]);
+    }
+    if (full) store4(P.theta + e, th);
+    else for (int k = 0; k < left; ++k) P.theta[e + k] = th[k];
+}
+
+template <int IN, bool KOUT>
+static hipError_t launch_tile(const AggParams &P, hipStream_t s)
+{
+    const unsigned grid = static_cast<unsigned>((P.n + 255) / 256);
+    if (P.n_seg > 0) tile_apply_kernel<IN, KOUT, true><<<grid, kTileThreads, 0, s>>>(P);
+    else tile_apply_kernel<IN, KOUT, false><<<grid, kTileThreads, 0, s>>>(P);
+    return hipGetLastError();
+}
+
 template <int IN, int GDT, bool APPLY, bool MOM, bool KOUT>
 static hipError_t launch_one(const AggParams &P, hipStream_t s)
 {
@@ -686,6 +856,17 @@ static hipError_t launch_in(const AggParams &P, bool apply, int g_dtype, hipStre
 // 2/4/8 fields, 16 ternary (pos + nz rows).  kout: counts wanted from 1-bit rows.
 hipError_t launch_aggregate(const AggParams &P, int in_kind, bool apply, bool kout, int g_dtype, hipStream_t s)
 {
+    // few workers, apply, no momentum streams, no planes wanted: one tile per wave
+    const bool tile_ok = apply && P.n_m == 0 && !P.vote_pos && !P.vote_nz;
+    if (tile_ok && (in_kind == IN_BITS || in_kind == IN_TERNARY) && P.W <= LC_TILE_MAX_W_BITS && !(kout && P.sum_bits == 1)) {
+        if (in_kind == IN_TERNARY) return launch_tile<IN_TERNARY, false>(P, s);
+        return kout ? launch_tile<IN_BITS, true>(P, s) : launch_tile<IN_BITS, false>(P, s);
+    }
+    if (tile_ok && LC_TILE_FIELDS && (in_kind == 2 || in_kind == 4 || in_kind == 8)) {
+        if (in_kind == 2) return launch_tile<2, false>(P, s);
+        if (in_kind == 4) return launch_tile<4, false>(P, s);
+        return launch_tile<8, false>(P, s);
+    }
     switch (in_kind) {
     case IN_PLANES:
         if (LC_APPLY_ONLY && apply && P.n_seg == 0 && !P.vote_pos && !P.vote_nz) return launch_apply_only(P, g_dtype, s);
