@@ -708,6 +708,25 @@ __global__ __launch_bounds__(kTileThreads) void tile_apply_kernel(const AggParam
     if (full) th = load4(P.theta + e);
     else for (int k = 0; k < left; ++k) th[k] = P.theta[e + k];
 
+    // Rates of the lane's group.  Placed here, between the issue of the theta loads and the
+    // row loads, so that the search (a chain of dependent scalar loads) runs while those
+    // are in flight; after the counting it would wait for them first.
+    float lr = P.lr, wd = P.wd;
+    if (GROUPED) {
+        // first group that ends beyond the tile's first 64-element block (uniform), then
+        // each lane walks on to the group of its own block
+        const uint32_t t64 = static_cast<uint32_t>(tile / 64);
+        int lo = 0, hi = P.n_seg - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (P.seg_end64[mid] > t64) hi = mid;
+            else lo = mid + 1;
+        }
+        const uint32_t e64 = static_cast<uint32_t>(e / 64);
+        while (lo < P.n_seg - 1 && e64 >= P.seg_end64[lo]) ++lo;
+        lr = P.seg_lr[lo];
+        wd = P.seg_wd[lo];
+    }
     // counts: byte k of kp = K (or K+) of element e + k, byte k of kn = K- (ternary only)
     uint32_t kp = 0, kn = 0;
     if constexpr (IN == IN_BITS || IN == IN_TERNARY) {
@@ -797,22 +816,6 @@ __global__ __launch_bounds__(kTileThreads) void tile_apply_kernel(const AggParam
         }
     }
 
-    float lr = P.lr, wd = P.wd;
-    if (GROUPED) {
-        // first group that ends beyond the tile's first 64-element block (uniform), then
-        // each lane walks on to the group of its own block
-        const uint32_t t64 = static_cast<uint32_t>(tile / 64);
-        int lo = 0, hi = P.n_seg - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (P.seg_end64[mid] > t64) hi = mid;
-            else lo = mid + 1;
-        }
-        const uint32_t e64 = static_cast<uint32_t>(e / 64);
-        while (lo < P.n_seg - 1 && e64 >= P.seg_end64[lo]) ++lo;
-        lr = P.seg_lr[lo];
-        wd = P.seg_wd[lo];
-    }
     // u per element: K against the threshold (or K+ against K-); what a tie gives is uniform
     const float tie_u = (IN == IN_TERNARY) ? 0.0f : (!P.tie_possible ? -1.0f : (P.tie < 0 ? 0.0f : (P.tie > 0 ? 1.0f : -1.0f)));
 #pragma unroll
