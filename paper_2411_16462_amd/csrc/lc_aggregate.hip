@@ -678,6 +678,10 @@ static hipError_t launch_apply_only(const AggParams &P, int g_dtype, hipStream_t
 // About W vector instructions per element: fine up to W = 32 (a budget of about 50 at
 // 8 TB/s); beyond that the bit-sliced kernel above takes over.
 constexpr int kTileThreads = 64;
+#ifndef LC_TILE_BATCH
+#define LC_TILE_BATCH 8
+#endif
+constexpr int kTileBatch = LC_TILE_BATCH;  // row loads in flight per lane
 #ifndef LC_TILE_MAX_W_BITS
 #define LC_TILE_MAX_W_BITS 32  // 1-bit and ternary rows: largest W served by the tile kernel (0 disables it)
 #endif
@@ -732,16 +736,21 @@ __global__ __launch_bounds__(kTileThreads) void tile_apply_kernel(const AggParam
     if constexpr (IN == IN_BITS || IN == IN_TERNARY) {
         // every byte that holds a bit of an element below n lies inside the row
         const size_t off = e / 8;
-        int w = 0;
-        for (; w + 8 <= W; w += 8) {
-            uint32_t x[8], z[8];
+        // kTileBatch rows at a time, all loads of a batch in flight together; a row index
+        // at or beyond W (uniform) loads nothing and counts as zero
+        for (int w = 0; w < W; w += kTileBatch) {
+            uint32_t x[kTileBatch], z[kTileBatch];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                x[i] = q8[static_cast<size_t>(w + i) * stride + off];
-                if (IN == IN_TERNARY) z[i] = z8[static_cast<size_t>(w + i) * stride + off];
+            for (int i = 0; i < kTileBatch; ++i) {
+                x[i] = 0;
+                z[i] = 0;
+                if (w + i < W) {
+                    x[i] = q8[static_cast<size_t>(w + i) * stride + off];
+                    if (IN == IN_TERNARY) z[i] = z8[static_cast<size_t>(w + i) * stride + off];
+                }
             }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < kTileBatch; ++i) {
                 if (IN == IN_TERNARY) {
                     kp += nibble_to_bytes(((x[i] & z[i]) >> sh) & 0xFu);
                     kn += nibble_to_bytes(((z[i] & ~x[i]) >> sh) & 0xFu);
@@ -750,42 +759,35 @@ __global__ __launch_bounds__(kTileThreads) void tile_apply_kernel(const AggParam
                 }
             }
         }
-        for (; w < W; ++w) {
-            const uint32_t x = q8[static_cast<size_t>(w) * stride + off];
-            if (IN == IN_TERNARY) {
-                const uint32_t z = z8[static_cast<size_t>(w) * stride + off];
-                kp += nibble_to_bytes(((x & z) >> sh) & 0xFu);
-                kn += nibble_to_bytes(((z & ~x) >> sh) & 0xFu);
-            } else {
-                kp += nibble_to_bytes((x >> sh) & 0xFu);
-            }
-        }
     } else {
         // IN-bit fields: the lane's four fields are IN / 2 bytes at byte e * IN / 8; in a
         // ragged lane only the bytes that hold elements below n are read
         const size_t off = e * IN / 8;
         const int bytes = full ? IN / 2 : (left * IN + 7) / 8;
         uint32_t acc = 0;
-        int w = 0;
         if (full) {
-            for (; w + 8 <= W; w += 8) {
-                uint32_t x[8];
+            for (int w = 0; w < W; w += kTileBatch) {
+                uint32_t x[kTileBatch];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const uint8_t *src = q8 + static_cast<size_t>(w + i) * stride + off;
-                    if (IN == 8) x[i] = *reinterpret_cast<const uint32_t *>(src);
-                    else if (IN == 4) x[i] = *reinterpret_cast<const uint16_t *>(src);
-                    else x[i] = *src;
+                for (int i = 0; i < kTileBatch; ++i) {
+                    x[i] = 0;
+                    if (w + i < W) {
+                        const uint8_t *src = q8 + static_cast<size_t>(w + i) * stride + off;
+                        if (IN == 8) x[i] = *reinterpret_cast<const uint32_t *>(src);
+                        else if (IN == 4) x[i] = *reinterpret_cast<const uint16_t *>(src);
+                        else x[i] = *src;
+                    }
                 }
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc += x[i];
+                for (int i = 0; i < kTileBatch; ++i) acc += x[i];
             }
-        }
-        for (; w < W; ++w) {
-            const uint8_t *src = q8 + static_cast<size_t>(w) * stride + off;
-            uint32_t x = 0;
-            for (int b = 0; b < bytes; ++b) x |= static_cast<uint32_t>(src[b]) << (8 * b);
-            acc += x;
+        } else {
+            for (int w = 0; w < W; ++w) {
+                const uint8_t *src = q8 + static_cast<size_t>(w) * stride + off;
+                uint32_t x = 0;
+                for (int b = 0; b < bytes; ++b) x |= static_cast<uint32_t>(src[b]) << (8 * b);
+                acc += x;
+            }
         }
         if (!full) acc &= (1u << (left * IN)) - 1u;  // fields of elements at and beyond n do not count
         if (IN == 8) kp = acc;
