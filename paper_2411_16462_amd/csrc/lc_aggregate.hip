@@ -266,18 +266,17 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
         const size_t step4 = stride * kPhases;
         const int np = 32 - __builtin_clz(static_cast<unsigned>(W));  // planes that hold a count up to W
         uint64_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        const int every = W / kPhases;                 // rows that exist for every phase
-        const int most = (W + kPhases - 1) / kPhases;  // rows of phase 0
-        int k = 0;
-        for (; k + 8 <= every; k += 8) {
+        const int most = (W + kPhases - 1) / kPhases;  // rows of phase 0; later phases may have one fewer
+        // eight rows at a time, their loads in flight together; a row that does not exist
+        // counts as zero
+        for (int k = 0; k < most; k += 8) {
             uint64_t x[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) x[i] = vm ? ld_packed(qp + static_cast<size_t>(k + i) * step4) : 0ull;
+            for (int i = 0; i < 8; ++i) {
+                const bool have = vm && (ph + (k + i) * kPhases < W);
+                x[i] = have ? ld_packed(qp + static_cast<size_t>(k + i) * step4) : 0ull;
+            }
             csa8(c, x);
-        }
-        for (; k < most; ++k) {
-            const bool have = vm && (ph + k * kPhases < W);
-            ripple(c, have ? ld_packed(qp + static_cast<size_t>(k) * step4) : 0ull, 0);
         }
 #pragma unroll
         for (int mask = kAggWords; mask < kWave; mask <<= 1) add_partner(c, lane, mask, np);
@@ -578,14 +577,12 @@ __global__ __launch_bounds__(kVoteThreads) void vote_only_kernel(const AggParams
     const size_t stride = P.q_stride_bytes / 8;
     const uint64_t *qp = static_cast<const uint64_t *>(P.q) + jw;
     uint64_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    int w = 0;
-    for (; w + 8 <= W; w += 8) {
+    for (int w = 0; w < W; w += 8) {  // a row index at or beyond W (uniform) counts as zero
         uint64_t x[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) x[i] = ld_packed(qp + static_cast<size_t>(w + i) * stride);
+        for (int i = 0; i < 8; ++i) x[i] = (w + i < W) ? ld_packed(qp + static_cast<size_t>(w + i) * stride) : 0ull;
         csa8(c, x);
     }
-    for (; w < W; ++w) ripple(c, ld_packed(qp + static_cast<size_t>(w) * stride), 0);
     uint64_t gt, eq, pos, nz;
     compare_planes(c, P.thresh, gt, eq);
     vote_planes(gt, eq, P.tie_possible != 0, P.tie, pos, nz);
