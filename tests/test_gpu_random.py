@@ -105,3 +105,72 @@ def test_random_ternary_and_l1(c):
         assert np.array_equal(lv[:, :n].cpu().numpy(), ref["fields"]) and untouched(lv, n)
         assert_close(case.theta.cpu().numpy(), ref["theta"], "theta (L1)")
         assert_close(case.m.cpu().numpy(), ref["m"], "momentum (L1)")
+
+
+def random_table(n, rng):
+    """A random group table over n elements: ascending ends in units of 64 elements, with
+    repeated ends (empty segments) now and then; the last end reaches n."""
+    n64 = (n + 63) // 64
+    G = int(rng.integers(1, 12))
+    ends = sorted(int(v) for v in rng.integers(0, n64 + 1, G - 1)) + [n64]
+    bounds = [0] + [min(e * 64, n) for e in ends]
+    return ends, bounds
+
+
+@pytest.mark.parametrize("c", configs(32, 31337), ids=lambda c: "cfg%d" % c["i"])
+def test_random_routes_agree(c):
+    """Every route to the same update gives the same bits, and all match the oracle: fused
+    vote+apply; vote to planes, then apply from planes (with the momentum update moved into
+    the apply); the counts K from 1-bit rows through the p-bit call; and one launch with a
+    random per-group table against the oracle applied segment by segment."""
+    hp = dict(beta1=c["beta1"], beta2=c["beta2"], lr=c["lr"], wd=c["wd"])
+    n, W, step, tie = c["n"], c["W"], c["step"], c["tie"]
+    nw = (n + 63) // 64
+    ogd = orc.BF16 if c["g_dtype"] == "bf16" else orc.F32
+    rng = np.random.default_rng(c["seed"])
+    a, b, d = make_case(c), make_case(c), make_case(c)
+    ref = orc.step_1bit(a.theta0, a.m0, a.g0, step=step, zero=c["zero"], tie=tie, g_dtype=ogd, **hp)
+    # route A: update+pack with the momentum update, fused vote+apply
+    qa, nbytes = hip_update_pack(a, hp, step, 1, c["zero"])
+    lc.lc_vote_apply_1bit(qa, qa.stride(0) // 8, W, n, step, tie, a.theta, hp["lr"], hp["wd"], None, 0, None, 0, lc.LC_F32, 0,
+                          hp["beta2"])
+    # route B: pack without touching m, planes out, apply from planes with all W momentum rows
+    qb, _ = hip_update_pack(b, hp, step, 1, c["zero"], update_m=False)
+    pos, nz = guarded(1, nw * 8, "cuda"), guarded(1, nw * 8, "cuda")
+    lc.lc_vote_1bit(qb, qb.stride(0) // 8, W, n, pos, nz, step, tie)
+    lc.lc_apply_update(b.theta, pos, nz, n, hp["lr"], hp["wd"], b.m, b.m.stride(0), b.g, b.g.stride(0), b.gd, W, hp["beta2"])
+    torch.cuda.synchronize()
+    assert torch.equal(qa, qb)
+    assert np.array_equal(words_of(pos, nw)[0], ref["pos"]) and np.array_equal(words_of(nz, nw)[0], ref["nz"])
+    assert untouched(pos, nw * 8) and untouched(nz, nw * 8)
+    assert torch.equal(a.theta, b.theta) and torch.equal(a.m, b.m)
+    assert_close(a.theta.cpu().numpy(), ref["theta"], "theta")
+    assert_close(a.m.cpu().numpy(), ref["m"], "momentum")
+    # route C: the counts K from the same 1-bit rows through the p-bit call (momentum fused in)
+    p = max(2, int(W).bit_length())
+    if p <= 8:
+        C = lc.lc_container_bits(p)
+        ksum = guarded(1, (n * C + 7) // 8, "cuda")
+        qd, _ = hip_update_pack(d, hp, step, 1, c["zero"], update_m=False)
+        lc.lc_pbit_sum_apply(qd, qd.stride(0), 1, W, n, p, ksum, step, tie, d.theta, hp["lr"], hp["wd"], d.m, d.m.stride(0),
+                             d.g, d.g.stride(0), d.gd, W, hp["beta2"])
+        torch.cuda.synchronize()
+        rp = orc.step_pbit(d.theta0, d.m0, d.g0, p=p, step=step, zero=c["zero"], tie=tie, g_dtype=ogd, **hp)
+        assert np.array_equal(ksum[0, :(n * C + 7) // 8].cpu().numpy(), rp["sum_fields"]) and untouched(ksum, (n * C + 7) // 8)
+        assert torch.equal(d.theta, a.theta) and torch.equal(d.m, a.m)
+    # route D: a random group table in one launch (no momentum streams), on fresh parameters
+    ends, bounds = random_table(n, rng)
+    G = len(ends)
+    lrs = [float(v) for v in rng.choice([0.0, 1e-5, 1e-4, 3e-3, 3e-2], G)]
+    wds = [float(v) for v in rng.choice([0.0, 1e-2, 0.1, 1.0], G)]
+    e = make_case(c)
+    end_t = torch.tensor(ends, dtype=torch.int32, device="cuda")
+    lr_t = torch.tensor(lrs, dtype=torch.float32, device="cuda")
+    wd_t = torch.tensor(wds, dtype=torch.float32, device="cuda")
+    lc.lc_vote_apply_1bit_groups(qa, qa.stride(0) // 8, W, n, step, tie, e.theta, end_t, lr_t, wd_t, G)
+    torch.cuda.synchronize()
+    want = np.empty(n, np.float64)
+    for s in range(G):
+        lo, hi = bounds[s], bounds[s + 1]
+        want[lo:hi] = orc.apply(e.theta0[lo:hi], ref["u"][lo:hi], lrs[s], wds[s])
+    assert_close(e.theta.cpu().numpy(), want, "theta with a random group table")
