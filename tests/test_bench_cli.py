@@ -1,0 +1,43 @@
+"""Host-side checks of bench.py that need no GPU: the one-GPU rule, the workload table and
+the bookkeeping of algorithmic bytes."""
+import os
+import subprocess
+import sys
+
+import bench
+from paper_2411_16462_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_workload_table_matches_the_benchmark_configurations():
+    w = {x.name.split("_")[0]: x for x in synth.workloads()}
+    assert w["c0"].n == 1 << 20 and w["c0"].W == 4 and w["c0"].mode == "1bit"
+    n_small = sum(s for _, s in synth.gpt2_tensors(768, 12))
+    n_medium = sum(s for _, s in synth.gpt2_tensors(1024, 24))
+    assert n_small == 124439808 and n_medium == 354823168                 # GPT-2 small / medium with tied head
+    assert (w["c1"].n, w["c1"].W, w["c1"].mode) == (n_small, 8, "1bit")
+    assert (w["c2"].n, w["c2"].W, w["c2"].mode, w["c2"].p, w["c2"].noise) == (n_small, 8, "pbit", 4, 0.5)
+    assert (w["c3"].n, w["c3"].W, w["c3"].g_dtype, w["c3"].momentum_avg) == (n_medium, 16, "bf16", True)
+    assert (w["c4"].n, w["c4"].W, w["c4"].mode, w["c4"].p, w["c4"].agree) == (1_300_000_000, 64, "prepacked", 7, 0.6)
+    for x in w.values():
+        assert (x.beta1, x.beta2, x.lr, x.wd) == (0.9, 0.99, 1e-4, 0.1)
+    assert all(sz % 64 == 0 for _, sz in synth.gpt2_tensors(768, 12))      # tensors start on group boundaries
+    assert len(synth.gpt2_tensors(768, 12)) == 148
+
+
+def test_traffic_summaries_cover_the_dominant_kernels():
+    """bench.py fills roofline.traffic from the committed counter summaries."""
+    for name, kernel in (("c1_gpt2s_w8_1bit", "local_update_pack"), ("c2_gpt2s_w8_p4", "local_update_pack"),
+                         ("c3_gpt2m_w16_bf16_1bit_mavg", "local_update_pack"),
+                         ("c4_1p3b_w64_prepacked", "vote_apply_1bit"), ("l1_gpt2s_w8_l15", "l1_quantize_pack")):
+        t = bench.read_traffic(name, kernel)
+        assert t is not None and t > 1e9, (name, kernel)
+    assert bench.read_traffic("no_such_workload", "x") is None
