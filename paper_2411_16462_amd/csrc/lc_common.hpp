@@ -109,6 +109,16 @@ struct Grad<LC_BF16> {
 __device__ __forceinline__ f32x4 load4(const float *p) { return ld_stream(reinterpret_cast<const f32x4 *>(p)); }
 __device__ __forceinline__ void store4(float *p, f32x4 v) { st_stream(reinterpret_cast<f32x4 *>(p), v); }
 
+// Index of the wave in its workgroup as a value the compiler knows to be uniform (it lives
+// in a scalar register), so that what depends on it -- tile bases, row pointers, the search
+// through a group table -- stays on the scalar unit and its loads in the scalar cache.
+// threadIdx.x / 64 alone is uniform too, but the compiler cannot tell and would make every
+// such load a vector load that waits behind the wave's streaming loads.
+__device__ __forceinline__ int wave_index()
+{
+    return __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) / kWave);
+}
+
 // Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by index.  This
 // remaps the workgroup index so that G consecutive chunks (G a power of two) run on the
 // same XCD; G = 0 or 1 leaves the order alone.  Only whole groups of 8 G workgroups are

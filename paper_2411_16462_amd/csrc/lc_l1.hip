@@ -168,7 +168,7 @@ __global__ __launch_bounds__(kL1Threads) void l1_abs_sum_kernel(const void *__re
 {
     __shared__ uint64_t s_limbs[kL1Limbs];
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = wave_index();
     const size_t w = blockIdx.y;
 
     // the range [first, n) this workgroup's accumulator covers, and which accumulator

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(R *kWave) void momentum_avg_kernel(float *__restric
 {
     __shared__ f32x4 part[R][kWave];
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = wave_index();
     const size_t e = static_cast<size_t>(blockIdx.x) * kAvgTile + lane * 4;
     f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
     if (e < n) {
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void momentum_divergence_kernel(const float *_
 {
     __shared__ double s_max[4];
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = wave_index();
     const size_t e = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
     double worst = 0.0;  // largest sum of squared deviations of this lane's elements
     if (e < n) {

@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kPackThreads) void local_update_pack_kernel(
     int zero_bit)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = wave_index();
     const size_t w = blockIdx.y;
     const size_t wave_base = pack_chunk_index(blockIdx.x, gridDim.x) * kPackBlock + static_cast<size_t>(wave) * kPackWave;
     if (wave_base >= n) return;
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kPackThreads) void local_update_pack_ternary_kernel
     float beta2, float omb2, uint64_t *__restrict__ pos, uint64_t *__restrict__ nz, size_t stride_words)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = wave_index();
     const size_t w = blockIdx.y;
     const size_t wave_base = pack_chunk_index(blockIdx.x, gridDim.x) * kPackBlock + static_cast<size_t>(wave) * kPackWave;
     if (wave_base >= n) return;
