@@ -57,3 +57,33 @@ def test_aggregate_theta_and_momentum_streams_are_non_temporal(tmp_path):
         fields8 = re.search(r"aggregate_kernelILi8E", name)        # byte fields: 16-byte plain loads of packed rows
         loads = [l for l in lines if "load_dwordx4" in l and l.endswith(" nt")]
         assert len(loads) >= 4 or fields8, name                     # the four theta tiles (plus m, g streams)
+
+
+def test_group_search_stays_on_the_scalar_unit(tmp_path):
+    """The search through a group table must use scalar loads (scalar cache, own wait
+    counter).  If the compiler cannot see that the tile base is uniform it turns them into
+    vector loads that wait behind the wave's streaming loads -- same results, 75 % more
+    time.  A scalar load whose base is not the kernel-argument pointer s[0:1] can only be a
+    table access."""
+    out = os.path.join(str(tmp_path), "agg.s")
+    flags = [f for f in hip_build.FLAGS if f not in ("-fPIC", "-Wall", "-Wextra")]
+    subprocess.check_call([hip_build.HIPCC, *flags, "-S", "--cuda-device-only", os.path.join(CSRC, "lc_aggregate.hip"), "-o", out],
+                          stderr=subprocess.DEVNULL)
+    table_loads, cur = {}, None
+    for line in open(out):
+        m = re.match(r"^(_ZN2lc\w+):", line)
+        if m:
+            cur = m.group(1)
+            table_loads[cur] = 0
+        elif cur and re.search(r"\bs_load_dword\s+s\d+,\s*s\[(?!0:1\])", line):
+            table_loads[cur] += 1
+        if line.startswith(".Lfunc_end"):
+            cur = None
+    grouped = {k: v for k, v in table_loads.items() if re.search(r"tile_apply_kernelILi\d+ELb[01]ELb1E", k)}
+    assert len(grouped) >= 6
+    for name, count in grouped.items():
+        assert count >= 1, "%s: the group search lost its scalar loads" % name
+    plain = {k: v for k, v in table_loads.items() if re.search(r"tile_apply_kernelILi\d+ELb[01]ELb0E", k)}
+    assert plain and all(v == 0 for v in plain.values())                # and the pattern does single out the search
+    general = {k: v for k, v in table_loads.items() if re.search(r"aggregate_kernelILi1ELi0ELb1ELb0ELb0E", k)}
+    assert general and all(v >= 1 for v in general.values())
