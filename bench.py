@@ -34,7 +34,7 @@ def parse():
                     help="1-bit and L1 workloads with a tensor list: one set of calls per tensor instead of one per "
                          "arena (shows the small-tensor launch overhead; not the headline configuration)")
     ap.add_argument("--groups", action="store_true",
-                    help="1-bit and L1 workloads with a tensor list: per-tensor learning rates (and, for L1, per-tensor "
+                    help="workloads with a tensor list (c1, c2, c3, l1, t2): per-tensor learning rates (and, for L1, per-tensor "
                          "scales) through the group-table entry points, still one launch set for the arena")
     ap.add_argument("--split", action="store_true",
                     help="pre-packed workload (c4): lc_vote_1bit then lc_apply_update, the two calls either side of "
@@ -68,6 +68,21 @@ class Kernel:
 
     def mean_ms(self):
         return sum(a.elapsed_time(b) for a, b in self.events) / max(1, len(self.events))
+
+
+def group_table(wl, torch, dev):
+    """Device arrays of a per-tensor group table: segment ends in units of 64 elements and a
+    rate / decay per tensor (matrices at the base rate, vectors -- biases, LayerNorm -- at 30x
+    and without decay)."""
+    ends, off = [], 0
+    for _, sz in wl.tensors:
+        off += sz
+        ends.append(off // 64)
+    is_vec = [sz < 8192 for _, sz in wl.tensors]
+    end64 = torch.tensor(ends, dtype=torch.int32, device=dev)
+    lr_t = torch.tensor([wl.lr * (30.0 if v else 1.0) for v in is_vec], dtype=torch.float32, device=dev)
+    wd_t = torch.tensor([0.0 if v else wl.wd for v in is_vec], dtype=torch.float32, device=dev)
+    return end64, lr_t, wd_t, len(ends)
 
 
 def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False):
@@ -141,20 +156,12 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
                                             q.stride(0) * 8, step_no[0], lc.LC_ZERO_ALT),
             W * n * (4 + gb + 4 + 1 / 8)))
         if groups and wl.tensors:
-            ends, off = [], 0
-            for _, sz in wl.tensors:
-                off += sz
-                ends.append(off // 64)
-            end64 = torch.tensor(ends, dtype=torch.int32, device=dev)
-            # matrices at the base rate, vectors (biases, LayerNorm) at 30x, no decay on vectors
-            is_vec = [sz < 8192 for _, sz in wl.tensors]
-            lr_t = torch.tensor([hp["lr"] * (30.0 if v else 1.0) for v in is_vec], dtype=torch.float32, device=dev)
-            wd_t = torch.tensor([0.0 if v else hp["wd"] for v in is_vec], dtype=torch.float32, device=dev)
+            end64, lr_t, wd_t, G = group_table(wl, torch, dev)
             st.update(end64=end64, lr_t=lr_t, wd_t=wd_t)
             kernels.append(Kernel(
                 "vote_apply_1bit_groups",
                 lambda: lc.lc_vote_apply_1bit_groups(q, q.stride(0), W, n, step_no[0], lc.LC_TIE_ZERO, theta, end64,
-                                                     lr_t, wd_t, len(ends)),
+                                                     lr_t, wd_t, G),
                 n * (W / 8 + 8)))
         else:
             kernels.append(Kernel(
@@ -171,11 +178,19 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
             lambda: lc.lc_local_update_pack_ternary(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], 1, hp["beta2"],
                                                     pos, nz, pos.stride(0)),
             W * n * (4 + gb + 4 + 2 / 8)))
-        kernels.append(Kernel(
-            "vote_apply_ternary",
-            lambda: lc.lc_vote_apply_ternary(pos, nz, pos.stride(0), W, n, theta, hp["lr"], hp["wd"], None, 0, None, 0,
-                                             lc.LC_F32, 0, hp["beta2"]),
-            n * (2 * W / 8 + 8)))
+        if groups and wl.tensors:
+            end64, lr_t, wd_t, G = group_table(wl, torch, dev)
+            st.update(end64=end64, lr_t=lr_t, wd_t=wd_t)
+            kernels.append(Kernel(
+                "vote_apply_ternary_groups",
+                lambda: lc.lc_vote_apply_ternary_groups(pos, nz, pos.stride(0), W, n, theta, end64, lr_t, wd_t, G),
+                n * (2 * W / 8 + 8)))
+        else:
+            kernels.append(Kernel(
+                "vote_apply_ternary",
+                lambda: lc.lc_vote_apply_ternary(pos, nz, pos.stride(0), W, n, theta, hp["lr"], hp["wd"], None, 0, None, 0,
+                                                 lc.LC_F32, 0, hp["beta2"]),
+                n * (2 * W / 8 + 8)))
     elif wl.mode == "l1":
         L = wl.levels
         q = torch.zeros((W, synth.round_up(n, 64)), dtype=torch.uint8, device=dev)
@@ -211,15 +226,7 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
             kernels.append(Kernel("level_sum_apply[per tensor]", sum_all, n * (W + 1 + 8)))
         elif groups and wl.tensors:
             # one scale, rate and decay per tensor, three launches for the whole arena
-            ends, off = [], 0
-            for _, sz in wl.tensors:
-                off += sz
-                ends.append(off // 64)
-            G = len(ends)
-            end64 = torch.tensor(ends, dtype=torch.int32, device=dev)
-            is_vec = [sz < 8192 for _, sz in wl.tensors]
-            lr_t = torch.tensor([hp["lr"] * (30.0 if v else 1.0) for v in is_vec], dtype=torch.float32, device=dev)
-            wd_t = torch.tensor([0.0 if v else hp["wd"] for v in is_vec], dtype=torch.float32, device=dev)
+            end64, lr_t, wd_t, G = group_table(wl, torch, dev)
             mean_g = torch.zeros((W, G), dtype=torch.float64, device=dev)
             ws_g = torch.zeros(lc.lc_l1_groups_workspace_words(W, G), dtype=torch.int64, device=dev)
             st.update(end64=end64, lr_t=lr_t, wd_t=wd_t, mean_abs=mean_g)
@@ -264,11 +271,20 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
             lambda: lc.lc_local_update_pack(g, g.stride(0), gd, m, m.stride(0), W, n, hp["beta1"], 1, hp["beta2"], C, q,
                                             q.stride(0), step_no[0], lc.LC_ZERO_ALT),
             W * n * (4 + gb + 4 + C / 8)))
-        kernels.append(Kernel(
-            "pbit_sum_apply",
-            lambda: lc.lc_pbit_sum_apply(q, q.stride(0), C, W, n, wl.p, sum_out, step_no[0], lc.LC_TIE_ZERO, theta,
-                                         hp["lr"], hp["wd"], None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
-            n * (W * C / 8 + C / 8 + 8)))
+        if groups and wl.tensors:
+            end64, lr_t, wd_t, G = group_table(wl, torch, dev)
+            st.update(end64=end64, lr_t=lr_t, wd_t=wd_t)
+            kernels.append(Kernel(
+                "pbit_sum_apply_groups",
+                lambda: lc.lc_pbit_sum_apply_groups(q, q.stride(0), C, W, n, wl.p, sum_out, step_no[0], lc.LC_TIE_ZERO,
+                                                    theta, end64, lr_t, wd_t, G),
+                n * (W * C / 8 + C / 8 + 8)))
+        else:
+            kernels.append(Kernel(
+                "pbit_sum_apply",
+                lambda: lc.lc_pbit_sum_apply(q, q.stride(0), C, W, n, wl.p, sum_out, step_no[0], lc.LC_TIE_ZERO, theta,
+                                             hp["lr"], hp["wd"], None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
+                n * (W * C / 8 + C / 8 + 8)))
     if wl.momentum_avg:
         kernels.append(Kernel("momentum_avg", lambda: lc.lc_momentum_avg(m, m.stride(0), W, n), n * W * 8))
     return kernels, st, step_no
@@ -357,6 +373,10 @@ def main():
     torch.cuda.set_device(0)
     wl = synth.workload(args.workload)
     kernels, st, step_no = build_step(wl, torch, lc, synth, args.per_tensor, args.groups, args.split)
+    names = [k.name for k in kernels]                  # what was built, not what was asked for
+    calls = ("per tensor" if any("[per tensor]" in x for x in names)
+             else "one flat arena, per-tensor rates" if any(x.endswith("_groups") for x in names)
+             else "vote, then apply from planes" if "apply_update" in names else "one flat arena")
     torch.cuda.synchronize()
     if args.copy_calibration:
         src = torch.empty(args.copy_calibration, dtype=torch.uint8, device="cuda").fill_(1)
@@ -421,9 +441,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "n_params": wl.n, "workers": wl.W, "mode": wl.mode, "p": wl.p,
                    "g_dtype": wl.g_dtype, "momentum_avg": wl.momentum_avg, "levels": wl.levels,
-                   "calls": "per tensor" if args.per_tensor else ("one flat arena, per-tensor rates" if args.groups
-                                                                  else ("vote, then apply from planes" if args.split
-                                                                        else "one flat arena")),
+                   "calls": calls,
                    "launch": "hip graph replay" if args.graph else "stream"},
         "step_alg_bytes": step_bytes, "step_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
