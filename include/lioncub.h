@@ -109,6 +109,18 @@ int lc_apply_update(float *theta, const uint64_t *vote_pos, const uint64_t *vote
                     const void *g, size_t g_stride_elems, int g_dtype, int n_m,
                     float beta2, void *stream);
 
+/* The step after a SUMMING allreduce (Section 3 "direct allreduce"; Appendix F.1): the
+ * fields were added across all workers by the collective, so one buffer of sums K arrives
+ * (field layout as above, field_bits = 2, 4 or 8) together with the number they have to
+ * be compared with: u = sign(2 K - total).  total = W for sums of 0/1 signs; total =
+ * 2 W L for sums of L1 level bytes (S = K - W L).  Needs 1 <= total <= 2^field_bits - 1
+ * (else LC_ERR_RANGE).  A tie (2 K = total) follows tie_rule.  Then theta, and the
+ * momentum rows if n_m > 0, as in lc_apply_update. */
+int lc_count_apply(const void *k_fields, int field_bits, size_t n, int total, uint64_t step,
+                   int tie_rule, float *theta, float lr, float wd, float *m,
+                   size_t m_stride_elems, const void *g, size_t g_stride_elems, int g_dtype,
+                   int n_m, float beta2, void *stream);
+
 /* Section 5, momentum synchronisation: every row becomes the mean of the W rows (what
  * an averaging allreduce leaves on every worker).  The W values of an element are summed
  * in fp32 (partial sums over interleaved subsets of the rows, then their sum), and the

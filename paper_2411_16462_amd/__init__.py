@@ -32,6 +32,7 @@ SIGNATURES = {
     "lc_vote_1bit": (_i, [_vp, _sz, _i, _sz, _vp, _vp, _u64, _i, _vp]),
     "lc_pbit_sum_sign": (_i, [_vp, _sz, _i, _i, _sz, _i, _vp, _vp, _vp, _u64, _i, _vp]),
     "lc_apply_update": (_i, [_vp, _vp, _vp, _sz, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
+    "lc_count_apply": (_i, [_vp, _i, _sz, _i, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
     "lc_momentum_avg": (_i, [_vp, _sz, _i, _sz, _vp]),
     "lc_momentum_divergence": (_i, [_vp, _sz, _i, _sz, _vp, _vp]),
     "lc_momentum_divergence_groups": (_i, [_vp, _sz, _i, _sz, _vp, _i, _vp, _vp]),
@@ -130,6 +131,12 @@ def lc_apply_update(theta, vote_pos, vote_nz, n, lr, wd, m, m_stride_elems, g, g
                     beta2, stream=None, check=True):
     return _call("lc_apply_update", check, _ptr(theta), _ptr(vote_pos), _ptr(vote_nz), n, lr, wd, _ptr(m),
                  m_stride_elems, _ptr(g), g_stride_elems, g_dtype, n_m, beta2, _stream(stream))
+
+
+def lc_count_apply(k_fields, field_bits, n, total, step, tie_rule, theta, lr, wd, m, m_stride_elems, g, g_stride_elems,
+                   g_dtype, n_m, beta2, stream=None, check=True):
+    return _call("lc_count_apply", check, _ptr(k_fields), field_bits, n, total, step, tie_rule, _ptr(theta), lr, wd,
+                 _ptr(m), m_stride_elems, _ptr(g), g_stride_elems, g_dtype, n_m, beta2, _stream(stream))
 
 
 def lc_momentum_avg(m, m_stride_elems, W, n, stream=None, check=True):

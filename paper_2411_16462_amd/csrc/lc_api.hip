@@ -204,6 +204,42 @@ int lc_apply_update(float *theta, const uint64_t *vote_pos, const uint64_t *vote
     return from_hip(launch_aggregate(P, 0, true, false, n_m > 0 ? g_dtype : LC_F32, static_cast<hipStream_t>(stream)));
 }
 
+int lc_count_apply(const void *k_fields, int field_bits, size_t n, int total, uint64_t step, int tie_rule, float *theta,
+                   float lr, float wd, float *m, size_t m_stride_elems, const void *g, size_t g_stride_elems, int g_dtype,
+                   int n_m, float beta2, void *stream)
+{
+    if (field_bits != 2 && field_bits != 4 && field_bits != 8) return LC_ERR_MODE;
+    if (tie_rule != LC_TIE_ZERO && tie_rule != LC_TIE_ALT) return LC_ERR_MODE;
+    if (total < 1 || total > (1 << field_bits) - 1) return LC_ERR_RANGE;
+    if (n > LC_MAX_N || n_m < 0 || n_m > LC_MAX_W) return LC_ERR_SIZE;
+    if (!k_fields || !theta) return LC_ERR_NULL;
+    if (!aligned(k_fields, 16) || !aligned(theta, 16)) return LC_ERR_ALIGN;
+    if (n_m > 0) {
+        const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, n_m);
+        if (rc) return rc;
+    }
+    if (n == 0) return LC_OK;
+    AggParams P{};
+    P.q = k_fields;
+    P.W = 1;
+    P.n = n;
+    P.sum_bits = field_bits;
+    P.tie = tie_code(tie_rule, step);
+    P.thresh = total >> 1;           // 2 K > total  <=>  K > floor(total / 2)
+    P.tie_possible = (total & 1) == 0;
+    P.theta = theta;
+    P.lr = lr;
+    P.wd = wd;
+    P.m = m;
+    P.m_stride = m_stride_elems;
+    P.g = g;
+    P.g_stride = g_stride_elems;
+    P.n_m = n_m;
+    P.beta2 = beta2;
+    P.omb2 = 1.0f - beta2;
+    return from_hip(launch_aggregate(P, field_bits, true, false, n_m > 0 ? g_dtype : LC_F32, static_cast<hipStream_t>(stream)));
+}
+
 int lc_momentum_avg(float *m, size_t m_stride_elems, int W, size_t n, void *stream)
 {
     if (W < 1 || W > LC_MAX_W || n > LC_MAX_N) return LC_ERR_SIZE;

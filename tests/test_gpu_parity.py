@@ -548,3 +548,46 @@ def test_groups_for_field_sums_and_ternary_votes(kind):
         off += sz
     assert (u == 0).any() and (u == 1).any() and (u == -1).any()
     assert_close(case.theta.cpu().numpy(), want, "theta with per-group rates (%s)" % kind)
+
+
+@pytest.mark.parametrize("p,W,n", [(2, 3, 4099), (4, 8, 70001), (4, 15, 255), (7, 100, 33333), (8, 255, 5000), (3, 6, 1)])
+@pytest.mark.parametrize("n_m", [0, 2])
+def test_count_apply_after_a_summing_allreduce(p, W, n, n_m):
+    """The direct-allreduce route of Section 3: the collective delivers the summed fields K,
+    the library compares them with the worker count and applies.  The sums come from the
+    oracle (what a summing allreduce over the W field buffers yields)."""
+    step, tie = 5, lc.LC_TIE_ZERO if n % 2 else lc.LC_TIE_ALT
+    case = Case(n, W, seed=18000 + p + W, noise=3.0)
+    case.g[:, ::5] = 0
+    case.m[:, ::5] = 0
+    case.snapshot()
+    ref = orc.step_pbit(case.theta0, case.m0, case.g0, p=p, step=step, tie=tie, **HP)
+    C = lc.lc_container_bits(p)
+    k = guarded(1, (n * C + 7) // 8, "cuda")
+    k[0, :(n * C + 7) // 8] = torch.from_numpy(ref["sum_fields"]).cuda()
+    n_rows = min(n_m, W)
+    lc.lc_count_apply(k, C, n, W, step, tie, case.theta, HP["lr"], HP["wd"], case.m if n_rows else None, case.m.stride(0),
+                      case.g if n_rows else None, case.g.stride(0), case.gd, n_rows, HP["beta2"])
+    torch.cuda.synchronize()
+    assert_close(case.theta.cpu().numpy(), ref["theta"], "theta from summed fields")
+    assert_close(case.m[:n_rows].cpu().numpy(), ref["m"][:n_rows], "momentum rows")
+    assert np.array_equal(case.m[n_rows:].cpu().numpy(), case.m0[n_rows:])
+    assert untouched(k, (n * C + 7) // 8)
+    assert lc.lc_count_apply(k, C, n, 1 << C, step, tie, case.theta, 1e-4, 0.1, None, 0, None, 0, lc.LC_F32, 0, 0.99,
+                             check=False) == lc.LC_ERR_RANGE
+    assert lc.lc_count_apply(k, 1, n, 1, step, tie, case.theta, 1e-4, 0.1, None, 0, None, 0, lc.LC_F32, 0, 0.99,
+                             check=False) == lc.LC_ERR_MODE
+
+
+def test_count_apply_on_summed_l1_levels():
+    """The 8-bit allreduce of Appendix F.1 sums level bytes; total = 2 W L."""
+    n, W, L, step = 50021, 8, 15, 4
+    case = Case(n, W, seed=18100, m_spread=1.0)
+    ref = orc.step_l1(case.theta0, case.m0, case.g0, L=L, step=step, tie=orc.TIE_ALT, **HP)
+    k = guarded(1, n, "cuda")
+    k[0, :n] = torch.from_numpy(ref["K"].astype(np.uint8)).cuda()
+    lc.lc_count_apply(k, 8, n, 2 * W * L, step, lc.LC_TIE_ALT, case.theta, HP["lr"], HP["wd"], None, 0, None, 0, lc.LC_F32, 0,
+                      HP["beta2"])
+    torch.cuda.synchronize()
+    assert (ref["S"] == 0).any()
+    assert_close(case.theta.cpu().numpy(), ref["theta"], "theta from summed level bytes")
