@@ -243,3 +243,23 @@ def test_element_and_group_count_limits():
     assert lc.lc_l1_quantize_pack_groups(A, 1024, lc.LC_F32, A, 1024, 4, 0, 0.9, 1, 0.99, 15, A, 3, A, A, 1024, stream=0,
                                          check=False) == lc.LC_OK
     assert lc.lc_l1_groups_workspace_words(8, 148) == 8 * 148 * lc.LC_L1_WORKSPACE_WORDS + 75
+
+
+def test_count_apply_validation():
+    a = dict(k_fields=A, field_bits=4, n=0, total=8, step=1, tie_rule=lc.LC_TIE_ZERO, theta=A, lr=1e-4, wd=0.1, m=None,
+             m_stride_elems=0, g=None, g_stride_elems=0, g_dtype=lc.LC_F32, n_m=0, beta2=0.99, stream=0, check=False)
+    assert lc.lc_count_apply(**a) == lc.LC_OK
+    assert lc.lc_count_apply(**{**a, "total": 15}) == lc.LC_OK
+    assert lc.lc_count_apply(**{**a, "total": 16}) == lc.LC_ERR_RANGE          # a nibble cannot hold 16
+    assert lc.lc_count_apply(**{**a, "total": 0}) == lc.LC_ERR_RANGE
+    assert lc.lc_count_apply(**{**a, "field_bits": 8, "total": 255}) == lc.LC_OK
+    assert lc.lc_count_apply(**{**a, "field_bits": 8, "total": 256}) == lc.LC_ERR_RANGE
+    assert lc.lc_count_apply(**{**a, "field_bits": 2, "total": 3}) == lc.LC_OK
+    assert lc.lc_count_apply(**{**a, "field_bits": 1, "total": 1}) == lc.LC_ERR_MODE
+    assert lc.lc_count_apply(**{**a, "field_bits": 3}) == lc.LC_ERR_MODE
+    assert lc.lc_count_apply(**{**a, "tie_rule": 2}) == lc.LC_ERR_MODE
+    assert lc.lc_count_apply(**{**a, "k_fields": None}) == lc.LC_ERR_NULL
+    assert lc.lc_count_apply(**{**a, "theta": None}) == lc.LC_ERR_NULL
+    assert lc.lc_count_apply(**{**a, "k_fields": A + 8}) == lc.LC_ERR_ALIGN
+    assert lc.lc_count_apply(**{**a, "n_m": 1}) == lc.LC_ERR_NULL             # momentum rows need m and g
+    assert lc.lc_count_apply(**{**a, "n": lc.LC_MAX_N + 1}) == lc.LC_ERR_SIZE
