@@ -303,3 +303,20 @@ def test_l1_groups_argument_checks():
     assert lc.lc_l1_groups_workspace_words(0, 5) == 0 and lc.lc_l1_groups_workspace_words(2, 3) == 2 * 3 * 384 + 2
     torch.cuda.synchronize()
     assert torch.equal(case.m.cpu(), torch.from_numpy(case.m0))           # rejected calls touch nothing
+
+
+def test_l1_groups_empty_range_and_single_worker():
+    """n = 0 gives zero means for every group; W = 1 works like any other count."""
+    G = 3
+    end_t = torch.tensor([0, 0, 0], dtype=torch.int32, device="cuda")
+    mean = torch.full((2, G), -1.0, dtype=torch.float64, device="cuda")
+    ws = torch.full((lc.lc_l1_groups_workspace_words(2, G),), -1, dtype=torch.int64, device="cuda")
+    case = Case(640, 2, seed=26500)
+    lc.lc_l1_mean_abs_groups(case.g, case.g.stride(0), case.gd, case.m, case.m.stride(0), 2, 0, 0.9, end_t, None, G, mean, ws)
+    torch.cuda.synchronize()
+    assert (mean == 0).all().item()
+    one = Case(64 * 9 + 3, 1, seed=26501)
+    heavy_tailed(one, 3, 2.0)
+    ends64 = [4, 10]
+    out = run_l1_groups(one, 127, 1, ends64)
+    check_l1_groups(one, out, 127, 1, ends64)

@@ -591,3 +591,25 @@ def test_count_apply_on_summed_l1_levels():
     torch.cuda.synchronize()
     assert (ref["S"] == 0).any()
     assert_close(case.theta.cpu().numpy(), ref["theta"], "theta from summed level bytes")
+
+
+def test_momentum_divergence_per_group_degenerate_cases():
+    """One worker has no divergence; n = 0 writes zeros; a single group equals the plain call."""
+    case = Case(5000, 1, seed=14600)
+    end_t = torch.tensor([10, 79], dtype=torch.int32, device="cuda")
+    out = torch.full((2,), -1.0, dtype=torch.float64, device="cuda")
+    lc.lc_momentum_divergence_groups(case.m, case.m.stride(0), 1, 5000, end_t, 2, out)
+    torch.cuda.synchronize()
+    assert out.tolist() == [0.0, 0.0]
+    many = Case(70001, 6, seed=14601, m_spread=0.4)
+    out.fill_(-1.0)
+    lc.lc_momentum_divergence_groups(many.m, many.m.stride(0), 6, 0, end_t, 2, out)
+    torch.cuda.synchronize()
+    assert out.tolist() == [0.0, 0.0]
+    one_end = torch.tensor([(70001 + 63) // 64], dtype=torch.int32, device="cuda")
+    a = torch.zeros(1, dtype=torch.float64, device="cuda")
+    b = torch.zeros(1, dtype=torch.float64, device="cuda")
+    lc.lc_momentum_divergence_groups(many.m, many.m.stride(0), 6, 70001, one_end, 1, a)
+    lc.lc_momentum_divergence(many.m, many.m.stride(0), 6, 70001, b)
+    torch.cuda.synchronize()
+    assert a.item() == b.item() and a.item() > 0
