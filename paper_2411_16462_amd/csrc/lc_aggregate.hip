@@ -1,7 +1,16 @@
 // W-way aggregation (majority vote over packed bits, or p-bit sum then sign) and the
-// apply step, as one kernel family (Algorithm 1 lines 4-6; Section 3; Appendix A.1, B.1
-// and F.1).
+// apply step (Algorithm 1 lines 4-6; Section 3; Appendix A.1, B.1 and F.1).
 //
+// Four kernels, chosen by launch_aggregate() at the end of this file:
+//   aggregate_kernel    the general one, described next: any input kind, any W, optional
+//                       planes / counts out, optional momentum streams;
+//   vote_only_kernel    1-bit rows in, planes out, nothing applied;
+//   apply_only_kernel   planes in, theta (and momentum rows) updated;
+//   tile_apply_kernel   aggregate + apply for few workers without momentum streams.
+// The last three are the general kernel's special cases with a wave shape that suits them
+// better; their results are the same bits.
+//
+// General kernel.
 // Every wave works alone on kAggWave = 1024 consecutive elements (16 packed words, four
 // 256-element tiles) and is short-lived: on MI355X many small independent waves stream
 // faster than few long ones.  Three phases:
