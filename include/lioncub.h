@@ -55,7 +55,8 @@ enum {
     LC_ERR_NULL = 1,  /* a required pointer is NULL                                      */
     LC_ERR_SIZE = 2,  /* W, n_m, n_groups or n (> LC_MAX_N) out of range                 */
     LC_ERR_ALIGN = 3, /* a base pointer or a row stride breaks the alignment rules       */
-    LC_ERR_RANGE = 4, /* p outside 1..8, or W > 2^p - 1 (the p-bit sum could overflow)   */
+    LC_ERR_RANGE = 4, /* the sums would not fit their fields: p outside 1..8, W > 2^p - 1,
+                         levels outside 1..127, 2 L W > 255, total > 2^field_bits - 1      */
     LC_ERR_DTYPE = 5, /* unknown gradient dtype                                          */
     LC_ERR_MODE = 6   /* unknown rule, out_bits / in_bits not one of the allowed widths  */
 };

@@ -473,7 +473,7 @@ const char *lc_status_string(int status)
     case LC_ERR_NULL: return "LC_ERR_NULL: a required pointer is NULL";
     case LC_ERR_SIZE: return "LC_ERR_SIZE: worker, row, group or element count out of range";
     case LC_ERR_ALIGN: return "LC_ERR_ALIGN: pointer or row stride misaligned";
-    case LC_ERR_RANGE: return "LC_ERR_RANGE: p outside 1..8 or W > 2^p - 1";
+    case LC_ERR_RANGE: return "LC_ERR_RANGE: the sums would not fit their fields (p outside 1..8, W > 2^p - 1, 2 L W > 255 or total too large)";
     case LC_ERR_DTYPE: return "LC_ERR_DTYPE: unknown gradient dtype";
     case LC_ERR_MODE: return "LC_ERR_MODE: unknown rule or bit width";
     default: return status < 0 ? "HIP runtime error (status = -hipError_t)" : "unknown status";
