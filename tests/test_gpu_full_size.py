@@ -228,3 +228,46 @@ def test_l1_workload_per_tensor_scales():
         assert np.array_equal(st["q"][:, lo:hi].cpu().numpy(), fields), "level bytes in [%d, %d)" % (lo, hi)
         assert_close(st["theta"][lo:hi].cpu().numpy(), theta_ref, "theta in [%d, %d)" % (lo, hi))
     assert int(st["q"][:, :n].max()) <= 2 * L and int(st["sum_out"][:n].max()) <= 2 * L * W
+
+
+def test_ternary_workload():
+    """GPT-2-small shapes, 8 workers, the two-plane ternary wire format of Appendix B.1 as
+    bench.py runs it: planes, theta and momenta on sampled windows, and over the whole
+    range the applied update against the planes' own counts."""
+    wl = synth.workload("t2")
+    kernels, st, step_no = bench.build_step(wl, torch, lc, synth)
+    n, W = wl.n, wl.W
+    nw = (n + 63) // 64
+    theta0 = st["theta"].clone()
+    m0 = torch.empty((W, n), dtype=torch.float32, device="cuda")
+    m0.copy_(st["m"])
+    for k in kernels:
+        k.fn()
+    torch.cuda.synchronize()
+    hp = dict(beta1=wl.beta1, beta2=wl.beta2, lr=wl.lr, wd=wl.wd)
+    for lo, hi in windows(n, wl.seed):
+        ref = orc.step_ternary(theta0[lo:hi].cpu().numpy(), host_rows(m0, lo, hi), host_rows(st["g"], lo, hi), **hp)
+        w0, w1 = lo // 64, (hi + 63) // 64
+        assert np.array_equal(st["pos"][:, w0:w1].cpu().numpy().view(np.uint64), ref["pos_w"]), "pos planes in [%d, %d)" % (lo, hi)
+        assert np.array_equal(st["nz"][:, w0:w1].cpu().numpy().view(np.uint64), ref["nz_w"]), "nz planes in [%d, %d)" % (lo, hi)
+        assert_close(st["theta"][lo:hi].cpu().numpy(), ref["theta"], "theta in [%d, %d)" % (lo, hi))
+        assert_close(host_rows(st["m"], lo, hi), ref["m"], "momentum in [%d, %d)" % (lo, hi))
+    # whole range: K+ and K- from population counts of the planes, per 64-element word:
+    # sum over the word of u = sum of sign(K+ - K-) cannot be checked per element cheaply,
+    # but unanimous words can: all workers pos on every bit -> every u = +1, no worker nz -> u = 0
+    pos, nz = st["pos"][:, :nw], st["nz"][:, :nw]
+    all_pos, any_nz = pos[0] & nz[0], nz[0].clone()
+    for w in range(1, W):
+        all_pos &= pos[w] & nz[w]
+        any_nz |= nz[w]
+    d = (st["theta"] - theta0 * (1.0 - wl.lr * wl.wd)) / wl.lr            # = -u up to rounding
+    assert float((d - d.round()).abs().max()) < 1e-2 and float(d.abs().max()) < 1.01
+    u_all = -d.round()
+    shifts = torch.arange(64, device="cuda", dtype=torch.int64)
+    for lo in range(0, nw, 1 << 22):
+        hi = min(nw, lo + (1 << 22))
+        count = min(n, hi * 64) - lo * 64
+        a = ((all_pos[lo:hi, None] >> shifts) & 1).view(-1)[:count].bool()
+        z = ((any_nz[lo:hi, None] >> shifts) & 1).view(-1)[:count].bool()
+        uu = u_all[lo * 64: lo * 64 + count]
+        assert bool((uu[a] == 1).all()) and bool((uu[~z] == 0).all())
