@@ -125,6 +125,18 @@ def test_reduction_only_workload():
                          st["m"], st["m"].stride(0), st["g"], st["g"].stride(0), lc.LC_F32, 1, wl.beta2)
     torch.cuda.synchronize()
     assert torch.equal(st["theta"], theta1) and torch.equal(st["m"], m1)      # both routes: same bits
+    # third route: planes out (the dedicated vote kernel), then apply from planes
+    st["theta"].copy_(theta0)
+    st["m"].copy_(m0)
+    pos = torch.zeros(nw + 8, dtype=torch.int64, device="cuda")
+    nzp = torch.zeros(nw + 8, dtype=torch.int64, device="cuda")
+    lc.lc_vote_1bit(q, q.stride(0), W, n, pos, nzp, step_no[0], lc.LC_TIE_ZERO)
+    lc.lc_apply_update(st["theta"], pos, nzp, n, wl.lr, wl.wd, st["m"], st["m"].stride(0), st["g"], st["g"].stride(0),
+                       lc.LC_F32, 1, wl.beta2)
+    torch.cuda.synchronize()
+    assert torch.equal(st["theta"], theta1) and torch.equal(st["m"], m1)
+    assert int(pos[nw:].abs().max()) == 0 and int(nzp[nw:].abs().max()) == 0
+    del pos, nzp
     for lo, hi in windows(n, wl.seed):
         words = q[:, lo // 64:(hi + 63) // 64].cpu().numpy().view(np.uint64)
         b = np.stack([orc.unpack_1bit(words[w], hi - lo) for w in range(W)])
