@@ -9,7 +9,8 @@
  *
  * Conventions that hold for every entry point
  *  - All data pointers are DEVICE pointers owned by the caller.  The library allocates
- *    nothing, keeps no state between calls, never frees or retains caller memory and
+ *    nothing, keeps no state between calls (lc_l1_mean_abs_static alone uses a static
+ *    device array of its own, see there), never frees or retains caller memory and
  *    never synchronises.  `stream` is a hipStream_t passed as void* (NULL = the null
  *    stream); every call only enqueues kernels on it and returns.
  *  - Row w of a per-worker buffer starts at base + w * stride.
@@ -232,6 +233,23 @@ int lc_vote_apply_ternary_groups(const uint64_t *pos, const uint64_t *nz, size_t
 int lc_l1_mean_abs(const void *g, size_t g_stride_elems, int g_dtype, const float *m,
                    size_t m_stride_elems, int W, size_t n, float beta1, double *mean_abs,
                    uint64_t *workspace, void *stream);
+
+/* lc_l1_mean_abs for callers that cannot allocate device memory or bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * workspace is a static device array inside the library (LC_L1_STATIC_MAX_W *
+ * LC_L1_WORKSPACE_WORDS uint64 = 192 KiB, held by every GPU the library runs on until the
+ * process ends), so the call takes inputs and outputs only and calls no allocating
+ * routine.  W > LC_L1_STATIC_MAX_W is refused with LC_ERR_SIZE; everything else, results
+ * included, is as in lc_l1_mean_abs.  The first call on a device looks the array's address
+ * up (make one call, n = 0 will do, before capturing a graph on that device); the
+ * device that owns `stream` must be the current one.  All calls on one GPU share that
+ * GPU's array: it is cleared at the start of every call, and two calls that overlap in
+ * time on one GPU (different streams, or different host threads without ordering) race
+ * and give wrong means -- order them on one stream or with events. */
+#define LC_L1_STATIC_MAX_W 64
+int lc_l1_mean_abs_static(const void *g, size_t g_stride_elems, int g_dtype, const float *m,
+                          size_t m_stride_elems, int W, size_t n, float beta1, double *mean_abs,
+                          void *stream);
 
 /* Per-group scales in one call (a scale per parameter tensor, as when each tensor is
  * quantised on its own): the range is cut into n_groups consecutive segments as in

@@ -19,6 +19,7 @@ LC_ZERO_ALT, LC_ZERO_POS, LC_ZERO_NEG = 0, 1, 2
 LC_TIE_ZERO, LC_TIE_ALT = 0, 1
 LC_MAX_W = 255
 LC_L1_WORKSPACE_WORDS = 384
+LC_L1_STATIC_MAX_W = 64
 LC_MAX_GROUPS = 1 << 20
 LC_MAX_N = 1 << 38
 
@@ -47,6 +48,7 @@ SIGNATURES = {
     "lc_vote_ternary": (_i, [_vp, _vp, _sz, _i, _sz, _vp, _vp, _vp]),
     "lc_vote_apply_ternary": (_i, [_vp, _vp, _sz, _i, _sz, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
     "lc_l1_mean_abs": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _vp, _vp, _vp]),
+    "lc_l1_mean_abs_static": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _vp, _vp]),
     "lc_l1_quantize_pack": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _i, _f, _i, _vp, _vp, _sz, _vp]),
     "lc_l1_groups_workspace_words": (_sz, [_i, _i]),
     "lc_l1_mean_abs_groups": (_i, [_vp, _sz, _i, _vp, _sz, _i, _sz, _f, _vp, _vp, _i, _vp, _vp, _vp]),
@@ -212,6 +214,11 @@ def lc_l1_mean_abs(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, m
                    check=True):
     return _call("lc_l1_mean_abs", check, _ptr(g), g_stride_elems, g_dtype, _ptr(m), m_stride_elems, W, n, beta1,
                  _ptr(mean_abs), _ptr(workspace), _stream(stream))
+
+
+def lc_l1_mean_abs_static(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, mean_abs, stream=None, check=True):
+    return _call("lc_l1_mean_abs_static", check, _ptr(g), g_stride_elems, g_dtype, _ptr(m), m_stride_elems, W, n,
+                 beta1, _ptr(mean_abs), _stream(stream))
 
 
 def lc_l1_quantize_pack(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, update_m, beta2, levels, mean_abs,

@@ -261,6 +261,18 @@ int lc_l1_mean_abs(const void *g, size_t g_stride_elems, int g_dtype, const floa
                                        L1Groups(), static_cast<hipStream_t>(stream)));
 }
 
+int lc_l1_mean_abs_static(const void *g, size_t g_stride_elems, int g_dtype, const float *m, size_t m_stride_elems, int W,
+                          size_t n, float beta1, double *mean_abs, void *stream)
+{
+    if (W < 1 || W > LC_L1_STATIC_MAX_W || n > LC_MAX_N) return LC_ERR_SIZE;
+    const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
+    if (rc) return rc;
+    if (!mean_abs) return LC_ERR_NULL;
+    if (!aligned(mean_abs, 8)) return LC_ERR_ALIGN;
+    return from_hip(launch_l1_mean_abs_static(g, g_stride_elems, g_dtype, m, m_stride_elems, W, n, beta1, mean_abs,
+                                              static_cast<hipStream_t>(stream)));
+}
+
 size_t lc_l1_groups_workspace_words(int W, int n_groups)
 {
     if (W < 1 || n_groups < 1) return 0;

@@ -27,6 +27,8 @@
 // bisection on the segment ends while its loads of m and g are in flight.
 #include "lc_launch.hpp"
 
+#include <mutex>
+
 namespace lc {
 
 #ifndef LC_L1_TILES
@@ -362,6 +364,49 @@ hipError_t launch_l1_mean_abs(const void *g, size_t g_stride, int g_dtype, const
     l1_finalize_kernel<<<static_cast<unsigned>((n_acc + 63) / 64), 64, 0, s>>>(workspace, static_cast<int>(n_acc), n, mean_abs,
                                                                                grp.end64, grp.count, G);
     return hipGetLastError();
+}
+
+// ---- pass 1 for callers that cannot allocate -------------------------------------------
+// The workspace of lc_l1_mean_abs as a file-scope device array: every GPU the library runs
+// on holds its own copy at its own address until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; kernels and launches always take
+// the resolved device pointer, which is looked up once per device (with that device
+// current) and kept.
+static __device__ __align__(256) uint64_t scratch[LC_L1_STATIC_MAX_W * kL1Slots * kL1Limbs];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+uint64_t *g_scratch_ptr[kMaxDevices];  // device address of `scratch` per device ordinal; null = not yet resolved
+}  // namespace
+
+static hipError_t static_workspace(uint64_t **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        uint64_t *p = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+hipError_t launch_l1_mean_abs_static(const void *g, size_t g_stride, int g_dtype, const float *m, size_t m_stride, int W,
+                                     size_t n, float beta1, double *mean_abs, hipStream_t s)
+{
+    uint64_t *ws = nullptr;
+    const hipError_t e = static_workspace(&ws);
+    if (e != hipSuccess) return e;
+    // the summing kernels clear the W accumulator sets they use first (a fill kernel, so the
+    // call can be captured into a graph), whatever the previous call left there
+    return launch_l1_mean_abs(g, g_stride, g_dtype, m, m_stride, W, n, beta1, mean_abs, ws, L1Groups(), s);
 }
 
 // ---- pass 2: levels --------------------------------------------------------------------

@@ -63,6 +63,9 @@ struct L1Groups {
 };
 hipError_t launch_l1_mean_abs(const void *g, size_t g_stride, int g_dtype, const float *m, size_t m_stride, int W, size_t n,
                               float beta1, double *mean_abs, uint64_t *workspace, const L1Groups &grp, hipStream_t s);
+// lc_l1_mean_abs with the library's own per-device workspace (W <= LC_L1_STATIC_MAX_W)
+hipError_t launch_l1_mean_abs_static(const void *g, size_t g_stride, int g_dtype, const float *m, size_t m_stride, int W,
+                                     size_t n, float beta1, double *mean_abs, hipStream_t s);
 hipError_t launch_l1_quantize_pack(const void *g, size_t g_stride, int g_dtype, float *m, size_t m_stride, int W, size_t n,
                                    float beta1, bool update_m, float beta2, int levels, const double *mean_abs, uint8_t *q,
                                    size_t q_stride_bytes, const L1Groups &grp, hipStream_t s);
