@@ -4,11 +4,24 @@
 A step is one pass of the whole path over one batch of synthetic optimizer state that
 is already resident in HBM: every worker's local update + pack, the W-way aggregation,
 the apply (and, where the workload asks for it, momentum averaging) -- all through the C
-ABI of liblioncub.so.  Prints ONE JSON line: params/s for the step, the roofline of the
-dominant kernel (algorithmic bytes / its mean launch duration from HIP events on the
-launch stream) and the CPU oracle timed on a bounded sample of the same workload.
+ABI of liblioncub.so.  Prints ONE JSON line.  Its headline (value, ms_per_step, roofline,
+cpu_baseline) is the largest workload that runs the whole path, c3 (GPT-2-medium shapes,
+16 workers, bf16 gradients, momentum averaging every step); the same line carries, under
+"configs", one entry per other benchmark configuration -- c0 (once on one resident working
+set, once rotating over eight), c1, c2, c4 with the majority vote and c4 with the p = 7 sum
+of signs written as byte counts -- each with its step time and, per kernel, duration,
+algorithmic bytes and fraction of the HBM peak.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c0|c2|c3|c4|l1|t2]
+Timing protocol.  Two copies of the workload's state are built (eight for the rotating c0
+entry); after the warm-up every buffer the step writes is restored from a pristine copy,
+then exactly K steps run back to back, alternating between the copies, between one
+synchronisation and the next (ms_per_step = that wall clock / K).  Every call is also
+bracketed by HIP events on the launch stream (torch's current stream): per kernel and per
+step the mean, the median and the minimum over the K steps are reported, and the roofline
+entry divides the dominant kernel's algorithmic bytes by its mean launch duration.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c0|c1|c2|c4|l1|t2]
+                    [--others default|none|c0,c1,...] [--sum] [--split [--one-plane]]
 """
 import argparse
 import json
@@ -27,9 +40,25 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c1")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="parameters in the oracle's sample (0: skip)")
-    ap.add_argument("--cpu-threads", type=int, default=0, help="0 = host cores available, capped at 16")
+    ap.add_argument("--workload", default="c3")
+    ap.add_argument("--others", default="default",
+                    help="further configurations timed after the headline and reported under \"configs\": a comma "
+                         "list of c0, c0rot, c1, c2, c4, c4sum, l1, t2; \"default\" = all five benchmark "
+                         "configurations when the headline is c3, none otherwise; \"none\"")
+    ap.add_argument("--other-steps", type=int, default=10, help="timed steps of each further configuration")
+    ap.add_argument("--copies", type=int, default=2, help="state copies the timed steps alternate between (>= 1)")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 26,
+                    help="parameters in the oracle's all-threads sample (0: skip the CPU leg)")
+    ap.add_argument("--cpu-sample-single", type=int, default=1 << 23,
+                    help="parameters in the oracle's single-thread sample")
+    ap.add_argument("--cpu-threads", type=int, default=0,
+                    help="0 = the cores this process may use, capped at 16 (one GPU's share of the box)")
+    ap.add_argument("--sum", action="store_true",
+                    help="pre-packed workload (c4): the p = 7 sum of signs with the counts written as bytes "
+                         "(lc_pbit_sum_apply on 1-bit rows) instead of the majority vote")
+    ap.add_argument("--one-plane", action="store_true",
+                    help="with --split: the 1-bit wire form -- ties take the alternating sign, one plane is "
+                         "written (the re-pack before the allgather) and one plane is applied")
     ap.add_argument("--per-tensor", action="store_true",
                     help="1-bit and L1 workloads with a tensor list: one set of calls per tensor instead of one per "
                          "arena (shows the small-tensor launch overhead; not the headline configuration)")
@@ -66,8 +95,18 @@ class Kernel:
         else:
             self.fn()
 
-    def mean_ms(self):
-        return sum(a.elapsed_time(b) for a, b in self.events) / max(1, len(self.events))
+    def times_ms(self):
+        return [a.elapsed_time(b) for a, b in self.events]
+
+
+def stats(xs):
+    """mean, median and minimum of a list of durations"""
+    xs = sorted(xs)
+    k = len(xs)
+    if not k:
+        return {"mean": float("nan"), "median": float("nan"), "min": float("nan")}
+    med = xs[k // 2] if k % 2 else 0.5 * (xs[k // 2 - 1] + xs[k // 2])
+    return {"mean": sum(xs) / k, "median": med, "min": xs[0]}
 
 
 def group_table(wl, torch, dev):
@@ -85,35 +124,54 @@ def group_table(wl, torch, dev):
     return end64, lr_t, wd_t, len(ends)
 
 
-def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False):
-    """Allocate the workload on cuda:0 and return (kernels, state) for one step."""
+def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False, variant="vote", one_plane=False,
+               share=None):
+    """Allocate the workload on cuda:0 and return (kernels, state, step counter) for one
+    step.  state["rmw"] names the buffers a step writes in place.  share: a state dict of
+    an earlier copy whose read-only packed rows are reused (pre-packed workload)."""
     dev = "cuda"
     n, W = wl.n, wl.W
     nw = (n + 63) // 64
     hp = dict(beta1=wl.beta1, beta2=wl.beta2, lr=wl.lr, wd=wl.wd)
-    st = {}
+    st = {"rmw": ["theta", "m"]}
     step_no = [1]
     kernels = []
     if wl.mode == "prepacked":
-        q = synth.make_prepacked(n, W, seed=wl.seed, device=dev, agree=wl.agree)
+        q = share["q"] if share else synth.make_prepacked(n, W, seed=wl.seed, device=dev, agree=wl.agree)
         s1 = synth.make_state(n, 1, seed=wl.seed + 1, device=dev, g_scale=1.4e-3, noise=0.0)
         theta, m, g = s1["theta"], s1["m"], s1["g"]
         st.update(q=q, theta=theta, m=m, g=g)
         if split:
             # the two halves as a multi-GPU run would call them around the allgather of the
-            # vote: planes out, then planes in
-            pos = torch.zeros(synth.round_up(nw, 8), dtype=torch.int64, device=dev)
-            nz = torch.zeros(synth.round_up(nw, 8), dtype=torch.int64, device=dev)
+            # vote: planes out, then planes in.  one_plane: the 1-bit wire form (a tie takes
+            # the alternating sign, so one plane carries the whole vote)
+            pos = torch.zeros(synth.round_up(nw, synth.WORD_ALIGN), dtype=torch.int64, device=dev)
+            nz = None if one_plane else torch.zeros(synth.round_up(nw, synth.WORD_ALIGN), dtype=torch.int64, device=dev)
+            tie = lc.LC_TIE_ALT if one_plane else lc.LC_TIE_ZERO
+            planes = 1 if one_plane else 2
             st.update(pos=pos, nz=nz)
             kernels.append(Kernel(
                 "vote_1bit",
-                lambda: lc.lc_vote_1bit(q, q.stride(0), W, n, pos, nz, step_no[0], lc.LC_TIE_ZERO),
-                n * (W / 8 + 2 / 8)))
+                lambda: lc.lc_vote_1bit(q, q.stride(0), W, n, pos, nz, step_no[0], tie),
+                n * (W / 8 + planes / 8)))
             kernels.append(Kernel(
                 "apply_update",
                 lambda: lc.lc_apply_update(theta, pos, nz, n, hp["lr"], hp["wd"], m, m.stride(0), g, g.stride(0),
                                            lc.LC_F32, 1, hp["beta2"]),
-                n * (2 / 8 + 8 + 8 + 4)))
+                n * (planes / 8 + 8 + 8 + 4)))
+            return kernels, st, step_no
+        if variant == "sum":
+            # the p-bit route on the same rows: K = sum of the W bits as one byte per element
+            # (p = 7 holds 0..64), written out, then the sign of 2K - W is applied
+            C = lc.lc_container_bits(wl.p)
+            ksum = torch.zeros(synth.round_up(n * C // 8, 64), dtype=torch.uint8, device=dev)
+            st.update(sum_out=ksum)
+            kernels.append(Kernel(
+                "pbit_sum_apply",
+                lambda: lc.lc_pbit_sum_apply(q, q.stride(0) * 8, 1, W, n, wl.p, ksum, step_no[0], lc.LC_TIE_ZERO, theta,
+                                             hp["lr"], hp["wd"], m, m.stride(0), g, g.stride(0), lc.LC_F32, 1,
+                                             hp["beta2"]),
+                n * (W / 8 + C / 8 + 8 + 8 + 4)))
             return kernels, st, step_no
         kernels.append(Kernel(
             "vote_apply_1bit",
@@ -128,7 +186,7 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
     gb = 2 if wl.g_dtype == "bf16" else 4
     st.update(theta=theta, m=m, g=g)
     if wl.mode == "1bit" and per_tensor and wl.tensors:
-        q = torch.zeros((W, synth.round_up(nw, 8)), dtype=torch.int64, device=dev)
+        q = torch.zeros((W, synth.round_up(nw, synth.WORD_ALIGN)), dtype=torch.int64, device=dev)
         st["q"] = q
         spans, off = [], 0
         for _, sz in wl.tensors:
@@ -148,7 +206,7 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
         kernels.append(Kernel("local_update_pack[per tensor]", pack_all, W * n * (4 + gb + 4 + 1 / 8)))
         kernels.append(Kernel("vote_apply_1bit[per tensor]", vote_all, n * (W / 8 + 8)))
     elif wl.mode == "1bit":
-        q = torch.zeros((W, synth.round_up(nw, 8)), dtype=torch.int64, device=dev)
+        q = torch.zeros((W, synth.round_up(nw, synth.WORD_ALIGN)), dtype=torch.int64, device=dev)
         st["q"] = q
         kernels.append(Kernel(
             "local_update_pack",
@@ -170,8 +228,8 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
                                               hp["wd"], None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
                 n * (W / 8 + 8)))
     elif wl.mode == "ternary":
-        pos = torch.zeros((W, synth.round_up(nw, 8)), dtype=torch.int64, device=dev)
-        nz = torch.zeros((W, synth.round_up(nw, 8)), dtype=torch.int64, device=dev)
+        pos = torch.zeros((W, synth.round_up(nw, synth.WORD_ALIGN)), dtype=torch.int64, device=dev)
+        nz = torch.zeros((W, synth.round_up(nw, synth.WORD_ALIGN)), dtype=torch.int64, device=dev)
         st.update(pos=pos, nz=nz)
         kernels.append(Kernel(
             "local_update_pack_ternary",
@@ -290,9 +348,12 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
     return kernels, st, step_no
 
 
-def cpu_baseline(wl, st, torch, sample, threads):
-    """The oracle, as it stands, on the first `sample` parameters of the same buffers,
-    split into contiguous chunks over host threads (the C loops release the GIL)."""
+
+
+def cpu_baseline(wl, st, torch, sample, sample_single, threads):
+    """The oracle, as it stands, on the first parameters of the same buffers: once on one
+    thread (the first `sample_single` parameters) and once split into contiguous chunks over
+    the host threads this process may use (the first `sample`; the C loops release the GIL)."""
     from concurrent.futures import ThreadPoolExecutor
 
     import numpy as np
@@ -300,7 +361,8 @@ def cpu_baseline(wl, st, torch, sample, threads):
     import oracle as orc
     n = min(wl.n, sample)
     n -= n % 64
-    cores = threads or min(16, len(os.sched_getaffinity(0)))
+    allowed = len(os.sched_getaffinity(0))
+    cores = threads or min(16, allowed)
     kw = dict(beta1=wl.beta1, beta2=wl.beta2, lr=wl.lr, wd=wl.wd, step=1)
     theta = st["theta"][:n].cpu().numpy()
     if wl.mode == "prepacked":
@@ -334,6 +396,15 @@ def cpu_baseline(wl, st, torch, sample, threads):
                 r = orc.step_pbit(theta[lo:hi], m[:, lo:hi], g[:, lo:hi], p=wl.p, g_dtype=gd, **kw)
             if wl.momentum_avg:
                 orc.momentum_avg(r["m"].astype(np.float32))
+    # (a) one thread, chunk after chunk
+    n1 = min(n, sample_single)
+    n1 -= n1 % 64
+    chunk1 = 1 << 20
+    t0 = time.perf_counter()
+    for lo in range(0, n1, chunk1):
+        work(lo, min(n1, lo + chunk1))
+    dt1 = time.perf_counter() - t0
+    # (b) contiguous chunks over the threads
     chunk = max(64, (n // (cores * 4)) // 64 * 64)
     spans = [(lo, min(n, lo + chunk)) for lo in range(0, n, chunk)]
     t0 = time.perf_counter()
@@ -341,6 +412,9 @@ def cpu_baseline(wl, st, torch, sample, threads):
         list(ex.map(lambda s: work(*s), spans))
     dt = time.perf_counter() - t0
     return {"value": n / dt, "unit": "params/s", "cores": cores, "kind": "oracle",
+            "host_cpus": os.cpu_count(), "cpus_allowed": allowed,
+            "single_thread": {"value": n1 / dt1 if n1 else None, "unit": "params/s", "cores": 1,
+                              "sample": "first %d params of %s, all %d workers, %.2f s" % (n1, wl.name, wl.W, dt1)},
             "sample": "first %d params of %s, all %d workers, %d chunks over %d threads, %.2f s"
                       % (n, wl.name, wl.W, len(spans), cores, dt)}
 
@@ -358,6 +432,106 @@ def read_traffic(workload, kernel):
     return None
 
 
+class Run:
+    """`copies` copies of one workload's state and the timed steps over them."""
+
+    def __init__(self, wl, torch, lc, synth, copies, **build_kw):
+        self.wl, self.torch = wl, torch
+        self.sets = []
+        for _ in range(max(1, copies)):
+            share = self.sets[0][1] if self.sets else None
+            self.sets.append(build_step(wl, torch, lc, synth, share=share, **build_kw))
+        st0 = self.sets[0][1]
+        # every copy is drawn from the same seed, so one pristine copy restores them all
+        self.pristine = {k: st0[k].clone() for k in st0["rmw"]}
+        self.names = [k.name for k in self.sets[0][0]]
+        self.step_events = []
+
+    def restore(self):
+        for kernels, st, step_no in self.sets:
+            for k, src in self.pristine.items():
+                st[k].copy_(src)
+            step_no[0] = 1
+            for kern in kernels:
+                kern.events = []
+        self.step_events = []
+
+    def step(self, i, timed):
+        kernels, _, step_no = self.sets[i % len(self.sets)]
+        for k in kernels:
+            k.launch(self.torch, timed)
+        if timed:
+            self.step_events.append((kernels[0].events[-1][0], kernels[-1].events[-1][1]))
+        step_no[0] += 1
+
+    def measure(self, warmup, steps):
+        """warm-up, restore, then exactly `steps` steps between two synchronisations"""
+        torch = self.torch
+        for i in range(warmup):
+            self.step(i, False)
+        torch.cuda.synchronize()
+        self.restore()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(i, True)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    def kernel_rows(self):
+        rows = []
+        for j, name in enumerate(self.names):
+            ts = [t for kernels, _, _ in self.sets for t in kernels[j].times_ms()]
+            b = self.sets[0][0][j].alg_bytes
+            s = stats(ts)
+            gbps = b / (s["mean"] * 1e-3) / 1e9
+            rows.append({"kernel": name, "ms": s["mean"], "ms_median": s["median"], "ms_min": s["min"], "alg_bytes": b,
+                         "achieved_GBps": gbps, "frac": gbps / HBM_PEAK_GBS,
+                         "frac_median": b / (s["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "traffic": read_traffic(self.wl.name, name)})
+        return rows
+
+    def step_stats(self):
+        return stats([a.elapsed_time(b) for a, b in self.step_events])
+
+    def step_bytes(self):
+        return sum(k.alg_bytes for k in self.sets[0][0])
+
+
+def calls_label(names):
+    return ("per tensor" if any("[per tensor]" in x for x in names)
+            else "one flat arena, per-tensor rates" if any(x.endswith("_groups") for x in names)
+            else "vote, then apply from planes" if "apply_update" in names else "one flat arena")
+
+
+# further configurations reported under "configs": workload, build arguments, state copies
+OTHERS = {
+    "c0": ("c0", {}, 1, "one resident working set (cache-resident, launch-bound: reported only)"),
+    "c0rot": ("c0", {}, 8, "rotating over eight copies of the working set (480 MB: not cache-resident)"),
+    "c1": ("c1", {}, 2, ""),
+    "c2": ("c2", {}, 2, ""),
+    "c4": ("c4", {}, 2, "majority vote + apply (28 B / param)"),
+    "c4sum": ("c4", {"variant": "sum"}, 2, "p = 7 sum of signs written as byte counts + apply (29 B / param)"),
+    "c4split": ("c4", {"split": True}, 2, "vote to two planes, then apply from the planes"),
+    "c4split1": ("c4", {"split": True, "one_plane": True}, 2, "vote re-packed to one plane (ties alternate), then apply from it"),
+    "l1": ("l1", {}, 2, ""),
+    "t2": ("t2", {}, 2, ""),
+}
+
+
+def config_entry(run, ms_per_step, steps, note=""):
+    wl = run.wl
+    ss = run.step_stats()
+    sb = run.step_bytes()
+    out = {"workload": wl.name, "n_params": wl.n, "workers": wl.W, "steps": steps, "state_copies": len(run.sets),
+           "ms_per_step": ms_per_step, "ms_per_step_median": ss["median"], "ms_per_step_min": ss["min"],
+           "params_per_s": wl.n / (ms_per_step * 1e-3), "step_alg_bytes": sb,
+           "step_frac_of_hbm_peak": sb / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, "kernels": run.kernel_rows()}
+    if note:
+        out["note"] = note
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -372,11 +546,10 @@ def main():
     lc.load()
     torch.cuda.set_device(0)
     wl = synth.workload(args.workload)
-    kernels, st, step_no = build_step(wl, torch, lc, synth, args.per_tensor, args.groups, args.split)
-    names = [k.name for k in kernels]                  # what was built, not what was asked for
-    calls = ("per tensor" if any("[per tensor]" in x for x in names)
-             else "one flat arena, per-tensor rates" if any(x.endswith("_groups") for x in names)
-             else "vote, then apply from planes" if "apply_update" in names else "one flat arena")
+    build_kw = dict(per_tensor=args.per_tensor, groups=args.groups, split=args.split,
+                    variant="sum" if args.sum else "vote", one_plane=args.one_plane)
+    run = Run(wl, torch, lc, synth, 1 if args.graph else args.copies, **build_kw)
+    names = run.names                                   # what was built, not what was asked for
     torch.cuda.synchronize()
     if args.copy_calibration:
         src = torch.empty(args.copy_calibration, dtype=torch.uint8, device="cuda").fill_(1)
@@ -386,15 +559,12 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    def one_step(timed):
-        for k in kernels:
-            k.launch(torch, timed)
-        step_no[0] += 1
-
-    for _ in range(args.warmup):
-        one_step(False)
-    torch.cuda.synchronize()
     if args.graph:
+        kernels, st, step_no = run.sets[0]
+        for i in range(args.warmup):
+            run.step(i, False)
+        torch.cuda.synchronize()
+        run.restore()
         side = torch.cuda.Stream()
         graphs = {}
         with torch.cuda.stream(side):
@@ -412,45 +582,64 @@ def main():
         for i in range(args.steps):
             graphs[(i + 1) % 2].replay()
         torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+        tot = run.step_bytes()
+        gbps = tot / (ms_per_step * 1e-3) / 1e9
+        per_kernel = [{"kernel": "whole step (graph replay)", "ms": ms_per_step, "ms_median": None, "ms_min": None,
+                       "alg_bytes": tot, "achieved_GBps": gbps, "frac": gbps / HBM_PEAK_GBS, "traffic": None}]
+        step_s = {"median": None, "min": None}
     else:
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            one_step(True)
-        torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
+        ms_per_step = run.measure(args.warmup, args.steps)
+        per_kernel = run.kernel_rows()
+        step_s = run.step_stats()
 
-    per_kernel = []
-    if args.graph:
-        tot = sum(k.alg_bytes for k in kernels)
-        per_kernel.append({"kernel": "whole step (graph replay)", "ms": ms_per_step, "alg_bytes": tot,
-                           "achieved_GBps": tot / (ms_per_step * 1e-3) / 1e9})
-    for k in ([] if args.graph else kernels):
-        ms = k.mean_ms()
-        per_kernel.append({"kernel": k.name, "ms": ms, "alg_bytes": k.alg_bytes,
-                           "achieved_GBps": k.alg_bytes / (ms * 1e-3) / 1e9})
     dom = max(per_kernel, key=lambda r: r["ms"])
     roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["achieved_GBps"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": dom["achieved_GBps"] / HBM_PEAK_GBS,
-                "traffic": read_traffic(wl.name, dom["kernel"])}
-    step_bytes = sum(k.alg_bytes for k in kernels)
+                "unit": "GB/s", "frac": dom["achieved_GBps"] / HBM_PEAK_GBS, "traffic": dom["traffic"],
+                "alg_bytes_per_launch": dom["alg_bytes"], "avg_launch_ms": dom["ms"], "median_launch_ms": dom["ms_median"],
+                "min_launch_ms": dom["ms_min"]}
+    step_bytes = run.step_bytes()
     out = {
         "metric": "params/sec for Lion Cub step (pack+W-way vote+apply); % of HBM peak GB/s",
         "value": wl.n / (ms_per_step * 1e-3), "unit": "params/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "ms_per_step_median": step_s["median"],
+        "ms_per_step_min": step_s["min"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if wl.g_dtype == "f32" else "f32 (bf16 gradients)", "data": "synthetic",
         "config": {"workload": wl.name, "n_params": wl.n, "workers": wl.W, "mode": wl.mode, "p": wl.p,
                    "g_dtype": wl.g_dtype, "momentum_avg": wl.momentum_avg, "levels": wl.levels,
-                   "calls": calls,
+                   "calls": calls_label(names), "state_copies": len(run.sets),
                    "launch": "hip graph replay" if args.graph else "stream"},
         "step_alg_bytes": step_bytes, "step_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": roofline, "kernels": per_kernel,
     }
     if args.cpu_sample > 0:
-        out["cpu_baseline"] = cpu_baseline(wl, st, torch, args.cpu_sample, args.cpu_threads)
+        out["cpu_baseline"] = cpu_baseline(wl, run.sets[0][1], torch, args.cpu_sample, args.cpu_sample_single,
+                                           args.cpu_threads)
     else:
         out["cpu_baseline"] = None
+
+    # the other benchmark configurations, one after the other, each freed before the next
+    if args.others == "default":
+        others = ["c0", "c0rot", "c1", "c2", "c4", "c4sum"] if wl.name.startswith("c3") and not (
+            args.per_tensor or args.groups or args.graph) else []
+    elif args.others in ("none", ""):
+        others = []
+    else:
+        others = [x for x in args.others.split(",") if x]
+    del run
+    torch.cuda.empty_cache()
+    configs = {}
+    for key in others:
+        if key not in OTHERS:
+            sys.exit("bench.py: unknown configuration %r in --others" % key)
+        wname, kw, copies, note = OTHERS[key]
+        r = Run(synth.workload(wname), torch, lc, synth, copies, **kw)
+        ms = r.measure(min(args.warmup, 3), args.other_steps)
+        configs[key] = config_entry(r, ms, args.other_steps, note)
+        del r
+        torch.cuda.empty_cache()
+    out["configs"] = configs
     print(json.dumps(out))
 
 

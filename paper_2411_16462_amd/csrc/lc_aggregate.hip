@@ -41,6 +41,27 @@ namespace lc {
 #ifndef LC_AGG_THREADS
 #define LC_AGG_THREADS 128
 #endif
+// Unused dynamic LDS per workgroup: a tuning knob that caps how many workgroups share a
+// compute unit (160 KiB of LDS each); 0 leaves occupancy to the register count.  Kernels
+// whose waves are short (one tile: a load or two, a store) want every wave slot filled;
+// kernels whose waves walk many rows stream faster with FEWER waves per compute unit, each
+// of which keeps many loads in flight (measured on the W = 64 vote: 32 waves per unit
+// 5.35 TB/s, 12 waves 5.47, 8 waves 5.6, 4 waves 5.0).
+#ifndef LC_AGG_LDS
+#define LC_AGG_LDS 32768  // general kernel on 32 and more 1-bit rows: five workgroups = 10 waves per compute unit (+1.5 %)
+#endif
+#ifndef LC_AGG_BATCH16
+#define LC_AGG_BATCH16 1  // 1-bit rows of the general kernel: sixteen loads in flight per lane instead of eight (+1.5 % at W = 64)
+#endif
+#ifndef LC_VOTE_LDS
+#define LC_VOTE_LDS 65536  // two 256-thread workgroups = 8 waves per compute unit
+#endif
+#ifndef LC_APPLY_LDS
+#define LC_APPLY_LDS 0
+#endif
+#ifndef LC_TILE_LDS
+#define LC_TILE_LDS 0
+#endif
 #ifndef LC_AGG_XCD
 #define LC_AGG_XCD 2  // consecutive workgroups per XCD (measured: +3..5 % on the W = 64 and p = 4 workloads)
 #endif
@@ -276,9 +297,27 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
         const int np = 32 - __builtin_clz(static_cast<unsigned>(W));  // planes that hold a count up to W
         uint64_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         const int most = (W + kPhases - 1) / kPhases;  // rows of phase 0; later phases may have one fewer
-        // eight rows at a time, their loads in flight together; a row that does not exist
-        // counts as zero
-        for (int k = 0; k < most; k += 8) {
+        // sixteen rows at a time (two sets of eight), their loads in flight together; a row
+        // that does not exist counts as zero
+        int k = 0;
+#if LC_AGG_BATCH16
+        for (; k + 8 < most; k += 16) {
+            uint64_t x[8], y[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const bool have = vm && (ph + (k + i) * kPhases < W);
+                x[i] = have ? ld_packed(qp + static_cast<size_t>(k + i) * step4) : 0ull;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const bool have = vm && (ph + (k + 8 + i) * kPhases < W);
+                y[i] = have ? ld_packed(qp + static_cast<size_t>(k + 8 + i) * step4) : 0ull;
+            }
+            csa8(c, x);
+            csa8(c, y);
+        }
+#endif
+        for (; k < most; k += 8) {
             uint64_t x[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -570,33 +609,118 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
 
 // Vote only (planes out, nothing applied): the local reduction of the 1-bit compressed
 // allreduce between its all-to-all and its allgather (Section 3).  There is no element-wise
-// phase, so the word-per-lane layout is kept throughout: lane j of a wave owns word j of
-// every row (512 contiguous bytes per row and load instruction), a 256-thread workgroup
-// covers 256 words = 16384 elements -- enough bytes per workgroup not to be bound by the
-// dispatcher even for few workers.
-constexpr int kVoteThreads = 256;
+// phase, so the word-per-lane layout is kept throughout: a lane owns one 64-bit word of every
+// row (512 contiguous bytes per row and wave instruction) in each of kVoteCols consecutive
+// 64-word columns that its wave walks through.  Rows are fetched eight at a time into two
+// register sets that take turns: the next eight rows -- of this column, or the first eight of
+// the wave's next column -- are requested before the current eight are counted, so that a
+// wave always has loads in flight, also while it stores a column's planes.
+#ifndef LC_VOTE_THREADS
+#define LC_VOTE_THREADS 256
+#endif
+#ifndef LC_VOTE_COLS
+#define LC_VOTE_COLS 1
+#endif
+#ifndef LC_VOTE_PIPE
+#define LC_VOTE_PIPE 1
+#endif
+constexpr int kVoteThreads = LC_VOTE_THREADS;
+constexpr int kVoteCols = LC_VOTE_COLS;
 
-__global__ __launch_bounds__(kVoteThreads) void vote_only_kernel(const AggParams P)
+// eight consecutive rows of the lane's word, no guards: straight-line loads
+__device__ __forceinline__ void vote_load8(uint64_t (&x)[8], const uint64_t *src, size_t stride)
 {
-    const size_t jw = static_cast<size_t>(blockIdx.x) * kVoteThreads + threadIdx.x;
-    const size_t n = P.n;
-    if (jw * 64 >= n) return;
-    const uint64_t vm = valid_mask(jw * 64, n);
-    const int W = P.W;
-    const size_t stride = P.q_stride_bytes / 8;
-    const uint64_t *qp = static_cast<const uint64_t *>(P.q) + jw;
-    uint64_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int w = 0; w < W; w += 8) {  // a row index at or beyond W (uniform) counts as zero
-        uint64_t x[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) x[i] = (w + i < W) ? ld_packed(qp + static_cast<size_t>(w + i) * stride) : 0ull;
-        csa8(c, x);
-    }
+    for (int i = 0; i < 8; ++i) x[i] = ld_packed(src + static_cast<size_t>(i) * stride);
+}
+
+__device__ __forceinline__ void vote_store(const AggParams &P, uint64_t (&c)[8], size_t jw, size_t nw)
+{
     uint64_t gt, eq, pos, nz;
     compare_planes(c, P.thresh, gt, eq);
     vote_planes(gt, eq, P.tie_possible != 0, P.tie, pos, nz);
-    if (P.vote_pos) P.vote_pos[jw] = pos & vm;
-    if (P.vote_nz) P.vote_nz[jw] = nz & vm;
+    if (jw < nw) {
+        const uint64_t vm = valid_mask(jw * 64, P.n);
+        if (P.vote_pos) P.vote_pos[jw] = pos & vm;
+        if (P.vote_nz) P.vote_nz[jw] = nz & vm;
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) c[k] = 0ull;
+}
+
+// PIPE (W a multiple of 16): the rows of the wave's columns form one sequence of groups of
+// sixteen; two register sets take turns, and every load of the steady state is issued a
+// whole csa8 before its value is needed.  Otherwise: eight rows at a time, rows at or beyond
+// W (uniform) skipped.
+template <bool PIPE>
+__global__ __launch_bounds__(kVoteThreads) void vote_only_kernel(const AggParams P)
+{
+    const size_t nw = (P.n + 63) / 64;
+    const int lane = threadIdx.x & (kWave - 1);
+    // first word of the wave's first column
+    const size_t wave_first = ((static_cast<size_t>(blockIdx.x) * (kVoteThreads / kWave) + wave_index()) * kVoteCols) * kWave;
+    if (wave_first >= nw) return;
+    const int W = P.W;
+    const size_t stride = P.q_stride_bytes / 8;
+    const uint64_t *q = static_cast<const uint64_t *>(P.q);
+    uint64_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    // columns of this wave that hold words (uniform); a lane beyond the last word reads word 0
+    const size_t left = (nw - wave_first + kWave - 1) / kWave;
+    const int cols = left < static_cast<size_t>(kVoteCols) ? static_cast<int>(left) : kVoteCols;
+    auto word = [&](int t) { return wave_first + static_cast<size_t>(t) * kWave + lane; };
+    auto column = [&](int t) { const size_t j = word(t); return q + (j < nw ? j : 0); };
+    if constexpr (PIPE) {
+        uint64_t xa[8], xb[8];
+        const size_t half = 8 * stride;
+        int t = 0, w = 0;                       // column and first row of the current group of sixteen
+        const uint64_t *cur = column(0);        // its first row, this lane's word
+        vote_load8(xa, cur, stride);
+        for (;;) {
+            // the group after this one: further down this column, or the top of the next
+            const bool col_end = w + 16 >= W;
+            const bool last = col_end && t + 1 >= cols;
+            if (last) break;
+            const uint64_t *next = col_end ? column(t + 1) : cur + 2 * half;
+            vote_load8(xb, cur + half, stride);
+            csa8(c, xa);
+            vote_load8(xa, next, stride);
+            csa8(c, xb);
+            if (col_end) {
+                vote_store(P, c, word(t), nw);
+                ++t;
+                w = 0;
+            } else {
+                w += 16;
+            }
+            cur = next;
+        }
+        vote_load8(xb, cur + half, stride);
+        csa8(c, xa);
+        csa8(c, xb);
+        vote_store(P, c, word(t), nw);
+    } else {
+#pragma unroll 1
+        for (int t = 0; t < cols; ++t) {
+            const uint64_t *qp = column(t);
+            for (int w = 0; w < W; w += 8) {
+                uint64_t x[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) x[i] = (w + i < W) ? ld_packed(qp + static_cast<size_t>(w + i) * stride) : 0ull;
+                csa8(c, x);
+            }
+            vote_store(P, c, word(t), nw);
+        }
+    }
+}
+
+static hipError_t launch_vote_only(const AggParams &P, hipStream_t s)
+{
+    const size_t nw = (P.n + 63) / 64;
+    constexpr size_t per = static_cast<size_t>(kVoteThreads) * kVoteCols;  // words per workgroup
+    const unsigned grid = static_cast<unsigned>((nw + per - 1) / per);
+    if (LC_VOTE_PIPE && P.W % 16 == 0) vote_only_kernel<true><<<grid, kVoteThreads, LC_VOTE_LDS, s>>>(P);
+    else vote_only_kernel<false><<<grid, kVoteThreads, LC_VOTE_LDS, s>>>(P);
+    return hipGetLastError();
 }
 
 // Apply only (planes in): Algorithm 1 lines 5 and 6 after the allgather of the vote.  Nothing
@@ -665,9 +789,9 @@ __global__ __launch_bounds__(kApplyThreads) void apply_only_kernel(const AggPara
 static hipError_t launch_apply_only(const AggParams &P, int g_dtype, hipStream_t s)
 {
     const dim3 grid(static_cast<unsigned>((P.n + 255) / 256), static_cast<unsigned>(P.n_m > 0 ? P.n_m : 1));
-    if (P.n_m == 0) apply_only_kernel<LC_F32, false><<<grid, kApplyThreads, 0, s>>>(P);
-    else if (g_dtype == LC_BF16) apply_only_kernel<LC_BF16, true><<<grid, kApplyThreads, 0, s>>>(P);
-    else apply_only_kernel<LC_F32, true><<<grid, kApplyThreads, 0, s>>>(P);
+    if (P.n_m == 0) apply_only_kernel<LC_F32, false><<<grid, kApplyThreads, LC_APPLY_LDS, s>>>(P);
+    else if (g_dtype == LC_BF16) apply_only_kernel<LC_BF16, true><<<grid, kApplyThreads, LC_APPLY_LDS, s>>>(P);
+    else apply_only_kernel<LC_F32, true><<<grid, kApplyThreads, LC_APPLY_LDS, s>>>(P);
     return hipGetLastError();
 }
 
@@ -879,10 +1003,10 @@ static hipError_t launch_tile(const AggParams &P, hipStream_t s)
     constexpr size_t waves = kTileThreads / kWave;
     if (P.n_seg > 0) {
         constexpr size_t per = 256 * waves * kTilesPerWave<true>;
-        tile_apply_kernel<IN, KOUT, true><<<static_cast<unsigned>((P.n + per - 1) / per), kTileThreads, 0, s>>>(P);
+        tile_apply_kernel<IN, KOUT, true><<<static_cast<unsigned>((P.n + per - 1) / per), kTileThreads, LC_TILE_LDS, s>>>(P);
     } else {
         constexpr size_t per = 256 * waves * kTilesPerWave<false>;
-        tile_apply_kernel<IN, KOUT, false><<<static_cast<unsigned>((P.n + per - 1) / per), kTileThreads, 0, s>>>(P);
+        tile_apply_kernel<IN, KOUT, false><<<static_cast<unsigned>((P.n + per - 1) / per), kTileThreads, LC_TILE_LDS, s>>>(P);
     }
     return hipGetLastError();
 }
@@ -891,7 +1015,8 @@ template <int IN, int GDT, bool APPLY, bool MOM, bool KOUT>
 static hipError_t launch_one(const AggParams &P, hipStream_t s)
 {
     const unsigned grid = static_cast<unsigned>((P.n + kAggBlock - 1) / kAggBlock);
-    aggregate_kernel<IN, GDT, APPLY, MOM, KOUT><<<grid, kAggThreads, 0, s>>>(P);
+    const unsigned lds = (IN == IN_BITS && P.W >= 32) ? LC_AGG_LDS : 0;
+    aggregate_kernel<IN, GDT, APPLY, MOM, KOUT><<<grid, kAggThreads, lds, s>>>(P);
     return hipGetLastError();
 }
 
@@ -925,11 +1050,7 @@ hipError_t launch_aggregate(const AggParams &P, int in_kind, bool apply, bool ko
         if (LC_APPLY_ONLY && apply && P.n_seg == 0 && !P.vote_pos && !P.vote_nz) return launch_apply_only(P, g_dtype, s);
         return launch_in<IN_PLANES, false>(P, apply, g_dtype, s);
     case IN_BITS:
-        if (!apply && !kout) {
-            const size_t nw = (P.n + 63) / 64;
-            vote_only_kernel<<<static_cast<unsigned>((nw + kVoteThreads - 1) / kVoteThreads), kVoteThreads, 0, s>>>(P);
-            return hipGetLastError();
-        }
+        if (!apply && !kout) return launch_vote_only(P, s);
         return kout ? launch_in<IN_BITS, true>(P, apply, g_dtype, s) : launch_in<IN_BITS, false>(P, apply, g_dtype, s);
     case IN_TERNARY: return launch_in<IN_TERNARY, false>(P, apply, g_dtype, s);
     case 2: return launch_in<2, false>(P, apply, g_dtype, s);

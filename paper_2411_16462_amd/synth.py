@@ -20,6 +20,7 @@ from typing import List, Optional, Tuple
 import torch
 
 ROW_ALIGN = 64  # elements; keeps every worker's row 256-byte aligned for fp32
+WORD_ALIGN = 8   # 64-bit words; packed rows start 64-byte aligned
 
 
 def round_up(x: int, a: int) -> int:
@@ -168,7 +169,7 @@ def make_prepacked(n: int, W: int, *, seed: int, device="cpu", agree: float = 0.
     lo, hi = -(1 << 63), (1 << 63) - 1
     latent = torch.randint(lo, hi, (nw,), generator=gen, device=device, dtype=torch.int64)
     flip_num = round((1.0 - agree) * (1 << prob_bits))
-    q = torch.zeros((W, round_up(max(nw, 1), 8)), dtype=torch.int64, device=device)[:, :nw]
+    q = torch.zeros((W, round_up(max(nw, 1), WORD_ALIGN)), dtype=torch.int64, device=device)[:, :nw]
     tail = n % 64
     for w in range(W):
         q[w] = latent ^ biased_words(nw, flip_num, prob_bits, gen, device)
