@@ -145,3 +145,69 @@ def test_l1_with_one_level_is_not_the_sign():
     x = np.array([3.0, -3.0, 0.9, -0.9, 1.0, 1.1], np.float32)
     M = orc.mean_abs(x)                                          # 1.65
     assert orc.l1_levels(x, M, 1).tolist() == [1, -1, 0, 0, 0, 0]
+
+
+def _round_to_binary32(q):
+    """A rational rounded once to the nearest binary32 (ties to even), as a Fraction; the
+    inputs here stay inside the normal range, where numpy's float64 -> float32 conversion
+    after an exact float64 representation would round twice, so the rounding is done by hand."""
+    if q == 0:
+        return Fraction(0)
+    sign = -1 if q < 0 else 1
+    a = abs(q)
+    e = a.numerator.bit_length() - a.denominator.bit_length()           # 2^e <= a < 2^(e+2) roughly
+    while Fraction(2) ** e > a:
+        e -= 1
+    while Fraction(2) ** (e + 1) <= a:
+        e += 1
+    e = max(e, -126)                                                    # denormals share the exponent of 2^-126
+    ulp = Fraction(2) ** (e - 23)
+    k = a / ulp
+    lo = k.numerator // k.denominator
+    rem = k - lo
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and lo % 2 == 1):
+        lo += 1
+    return sign * lo * ulp
+
+
+@pytest.mark.parametrize("beta1", [0.5, 0.9, 0.95])
+def test_local_c_is_the_fma_of_the_rounded_product(beta1):
+    """Algorithm 1 line 3 in the pinned fp32 order: c = fl32(beta1 * m + fl32(fl32(1 - beta1) * g)),
+    the inner product rounded once, the sum of the exact product beta1 * m and that value
+    rounded once (a fused multiply-add).  Rebuilt with rationals on ordinary and on
+    near-cancelling inputs, with m != 0: a separate multiply and add, a swapped weight or an
+    unrounded (1 - beta1) all give other bits here.  The sign of c is the sign the 1-bit
+    path packs."""
+    rng = np.random.default_rng(int(beta1 * 100))
+    n = 1500
+    b1 = np.float32(beta1)
+    omb1 = np.float32(1.0) - b1
+    m = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    g = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    g[:500] = (-(b1 * m[:500]) / omb1).astype(np.float32)               # c within a few ulps of zero
+    g[500:750] = np.nextafter(g[:250], np.float32(1.0))
+    g[750:760] = 0.0
+    m[760:770] = 0.0
+    c = orc.local_c(m, g, beta1)
+    assert c.dtype == np.float32
+    want = []
+    for mi, gi in zip(m.tolist(), g.tolist()):
+        t = _round_to_binary32(Fraction(float(omb1)) * Fraction(gi))
+        want.append(_round_to_binary32(Fraction(float(b1)) * Fraction(mi) + t))
+    assert [Fraction(float(v)) for v in c.tolist()] == want
+    assert np.array_equal(np.sign(c).astype(np.int8), orc.local_sign(m, g, beta1))
+    # what the planted mistakes would give differs on these inputs
+    mul_add = (b1 * m).astype(np.float32) + (omb1 * g).astype(np.float32)
+    if beta1 != 0.5:                      # beta1 = 1/2 makes the product exact: both orders agree
+        assert np.any(mul_add.astype(np.float32) != c)
+    swapped = orc.local_c(g, m, beta1)
+    assert np.any(swapped != c)
+
+
+def test_round_to_binary32_helper_matches_numpy_on_float64_inputs():
+    """The helper against numpy's single rounding float64 -> float32."""
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal(2000) * np.exp2(rng.integers(-100, 100, 2000))
+    x[:4] = [2.0 ** -130, 1.0 + 2.0 ** -24, 1.0 + 3 * 2.0 ** -24, -(2.0 ** -127) * 1.5]
+    for v in x.tolist():
+        assert _round_to_binary32(Fraction(v)) == Fraction(float(np.float32(v)))
