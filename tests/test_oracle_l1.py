@@ -170,7 +170,7 @@ def _round_to_binary32(q):
     return sign * lo * ulp
 
 
-@pytest.mark.parametrize("beta1", [0.5, 0.9, 0.95])
+@pytest.mark.parametrize("beta1", [0.75, 0.9, 0.95])
 def test_local_c_is_the_fma_of_the_rounded_product(beta1):
     """Algorithm 1 line 3 in the pinned fp32 order: c = fl32(beta1 * m + fl32(fl32(1 - beta1) * g)),
     the inner product rounded once, the sum of the exact product beta1 * m and that value
@@ -198,8 +198,7 @@ def test_local_c_is_the_fma_of_the_rounded_product(beta1):
     assert np.array_equal(np.sign(c).astype(np.int8), orc.local_sign(m, g, beta1))
     # what the planted mistakes would give differs on these inputs
     mul_add = (b1 * m).astype(np.float32) + (omb1 * g).astype(np.float32)
-    if beta1 != 0.5:                      # beta1 = 1/2 makes the product exact: both orders agree
-        assert np.any(mul_add.astype(np.float32) != c)
+    assert np.any(mul_add.astype(np.float32) != c)
     swapped = orc.local_c(g, m, beta1)
     assert np.any(swapped != c)
 
