@@ -33,7 +33,9 @@
  *    alternating rule of Appendix B.1 (zero -> +1 on odd iterations, -1 on even ones).
  *  - Buffers named in one call must not overlap each other.
  *  - Return value: LC_OK, or a positive LC_ERR_* found on the host before anything was
- *    launched (nothing was written), or -(hipError_t) if a launch failed.
+ *    launched (nothing was written), or -(hipError_t) if a launch failed.  The status is
+ *    that of this call's own launches: an error that an earlier, unrelated HIP call of
+ *    the host program left pending is neither reported here nor cleared.
  *  - Thread safety: re-entrant; calls on different streams may run concurrently as
  *    long as their buffers are disjoint.
  */
@@ -163,8 +165,16 @@ int lc_vote_apply_1bit(const uint64_t *q, size_t q_stride_words, int W, size_t n
  * whole arena: the range is cut into n_groups consecutive segments; segment s ends at
  * element 64 * group_end64[s] (ascending; the last end must reach n) and uses
  * group_lr[s], group_wd[s].  The three arrays live on the DEVICE (they are static for a
- * model: upload once).  No momentum streams.  One call per tensor gives the same result
- * but is launch-bound for small tensors. */
+ * model: upload once).  No momentum streams (the signature has none: momenta are updated
+ * by lc_local_update_pack, or by the forms without a group table).  One call per tensor
+ * gives the same result but is launch-bound for small tensors.
+ * Group tables in every *_groups call: n_groups in 1..LC_MAX_GROUPS, and n at most
+ * 64 * (2^32 - 1) elements (ends are 32-bit), else LC_ERR_SIZE.  The table itself lives on
+ * the device and is not validated.  Every kernel resolves it by one rule: a 64-element
+ * block belongs to the first segment whose end lies beyond it, and to the last segment if
+ * there is none -- so a last end short of n extends to n, and ends beyond n mean n.  A
+ * table whose ends do not ascend is not detected; which segment an element then falls in
+ * is unspecified (all accesses stay inside the caller's buffers). */
 int lc_vote_apply_1bit_groups(const uint64_t *q, size_t q_stride_words, int W, size_t n,
                               uint64_t step, int tie_rule, float *theta,
                               const uint32_t *group_end64, const float *group_lr,
@@ -261,7 +271,7 @@ int lc_l1_mean_abs_static(const void *g, size_t g_stride_elems, int g_dtype, con
  * a multiple of 64; NULL divides by the segment's length.  A count or length of 0 gives
  * 0.  workspace: lc_l1_groups_workspace_words(W, n_groups) uint64 on the device,
  * overwritten.  group_end64 and group_count live on the DEVICE. */
-size_t lc_l1_groups_workspace_words(int W, int n_groups); /* host only; 0 if an argument is < 1 */
+size_t lc_l1_groups_workspace_words(int W, int n_groups); /* utility, host only; 0 if an argument is < 1 */
 int lc_l1_mean_abs_groups(const void *g, size_t g_stride_elems, int g_dtype, const float *m,
                           size_t m_stride_elems, int W, size_t n, float beta1,
                           const uint32_t *group_end64, const uint64_t *group_count,
@@ -305,8 +315,12 @@ int lc_level_sum_apply_groups(const uint8_t *q, size_t q_stride_bytes, int W, si
                               const float *group_lr, const float *group_wd, int n_groups,
                               void *stream);
 
-/* Smallest field width of 1, 2, 4, 8 bits that holds a p-bit value; -1 if p is not in
- * 1..8.  Host only. */
+/* ---- Utilities (host only; they follow no passage of the paper) ------------------------
+ * lc_container_bits, lc_status_string, lc_version and lc_l1_groups_workspace_words above
+ * touch no device memory and launch nothing. */
+
+/* Smallest field width of 1, 2, 4, 8 bits that holds a p-bit value (the container rule of
+ * the p-bit layout above); -1 if p is not in 1..8. */
 int lc_container_bits(int p);
 
 /* Static, human-readable name of a status code returned by the calls above. */

@@ -492,22 +492,13 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
     // forward from there, which is rare.
     int seg0 = 0;
     if (APPLY && P.n_seg > 0) {
-        const uint32_t first = static_cast<uint32_t>(wave_base / 64);
-        int lo = 0, hi = P.n_seg - 1;  // first segment whose end lies beyond `first`
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (P.seg_end64[mid] > first) hi = mid;
-            else lo = mid + 1;
-        }
-        seg0 = lo;
+        seg0 = group_find(P.seg_end64, P.n_seg, static_cast<uint32_t>(wave_base / 64));
     }
     auto rates = [&](size_t e, float &lr, float &wd) {
         lr = P.lr;
         wd = P.wd;
         if (P.n_seg > 0) {
-            int sgm = seg0;
-            const uint32_t e64 = static_cast<uint32_t>(e / 64);
-            while (sgm < P.n_seg - 1 && e64 >= P.seg_end64[sgm]) ++sgm;
+            const int sgm = group_walk(P.seg_end64, P.n_seg, seg0, static_cast<uint32_t>(e / 64));
             lr = P.seg_lr[sgm];
             wd = P.seg_wd[sgm];
         }
@@ -718,9 +709,8 @@ static hipError_t launch_vote_only(const AggParams &P, hipStream_t s)
     const size_t nw = (P.n + 63) / 64;
     constexpr size_t per = static_cast<size_t>(kVoteThreads) * kVoteCols;  // words per workgroup
     const unsigned grid = static_cast<unsigned>((nw + per - 1) / per);
-    if (LC_VOTE_PIPE && P.W % 16 == 0) vote_only_kernel<true><<<grid, kVoteThreads, LC_VOTE_LDS, s>>>(P);
-    else vote_only_kernel<false><<<grid, kVoteThreads, LC_VOTE_LDS, s>>>(P);
-    return hipGetLastError();
+    if (LC_VOTE_PIPE && P.W % 16 == 0) return launch(vote_only_kernel<true>, grid, kVoteThreads, LC_VOTE_LDS, s, P);
+    return launch(vote_only_kernel<false>, grid, kVoteThreads, LC_VOTE_LDS, s, P);
 }
 
 // Apply only (planes in): Algorithm 1 lines 5 and 6 after the allgather of the vote.  Nothing
@@ -789,10 +779,9 @@ __global__ __launch_bounds__(kApplyThreads) void apply_only_kernel(const AggPara
 static hipError_t launch_apply_only(const AggParams &P, int g_dtype, hipStream_t s)
 {
     const dim3 grid(static_cast<unsigned>((P.n + 255) / 256), static_cast<unsigned>(P.n_m > 0 ? P.n_m : 1));
-    if (P.n_m == 0) apply_only_kernel<LC_F32, false><<<grid, kApplyThreads, LC_APPLY_LDS, s>>>(P);
-    else if (g_dtype == LC_BF16) apply_only_kernel<LC_BF16, true><<<grid, kApplyThreads, LC_APPLY_LDS, s>>>(P);
-    else apply_only_kernel<LC_F32, true><<<grid, kApplyThreads, LC_APPLY_LDS, s>>>(P);
-    return hipGetLastError();
+    if (P.n_m == 0) return launch(apply_only_kernel<LC_F32, false>, grid, kApplyThreads, LC_APPLY_LDS, s, P);
+    if (g_dtype == LC_BF16) return launch(apply_only_kernel<LC_BF16, true>, grid, kApplyThreads, LC_APPLY_LDS, s, P);
+    return launch(apply_only_kernel<LC_F32, true>, grid, kApplyThreads, LC_APPLY_LDS, s, P);
 }
 
 // Aggregate + apply for few workers, one 256-element tile per wave (no momentum streams).
@@ -882,17 +871,10 @@ __device__ __forceinline__ void tile_apply_one(const AggParams &P, size_t tile, 
     if (GROUPED) {
         // first group that ends beyond the tile's first 64-element block (uniform), then
         // each lane walks on to the group of its own block
-        const uint32_t t64 = static_cast<uint32_t>(tile / 64);
-        int lo = 0, hi = P.n_seg - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (P.seg_end64[mid] > t64) hi = mid;
-            else lo = mid + 1;
-        }
-        const uint32_t e64 = static_cast<uint32_t>(e / 64);
-        while (lo < P.n_seg - 1 && e64 >= P.seg_end64[lo]) ++lo;
-        lr = P.seg_lr[lo];
-        wd = P.seg_wd[lo];
+        const int first = group_find(P.seg_end64, P.n_seg, static_cast<uint32_t>(tile / 64));
+        const int sgm = group_walk(P.seg_end64, P.n_seg, first, static_cast<uint32_t>(e / 64));
+        lr = P.seg_lr[sgm];
+        wd = P.seg_wd[sgm];
     }
     // counts: byte k of kp = K (or K+) of element e + k, byte k of kn = K- (ternary only)
     uint32_t kp = 0, kn = 0;
@@ -1003,12 +985,10 @@ static hipError_t launch_tile(const AggParams &P, hipStream_t s)
     constexpr size_t waves = kTileThreads / kWave;
     if (P.n_seg > 0) {
         constexpr size_t per = 256 * waves * kTilesPerWave<true>;
-        tile_apply_kernel<IN, KOUT, true><<<static_cast<unsigned>((P.n + per - 1) / per), kTileThreads, LC_TILE_LDS, s>>>(P);
-    } else {
-        constexpr size_t per = 256 * waves * kTilesPerWave<false>;
-        tile_apply_kernel<IN, KOUT, false><<<static_cast<unsigned>((P.n + per - 1) / per), kTileThreads, LC_TILE_LDS, s>>>(P);
+        return launch(tile_apply_kernel<IN, KOUT, true>, static_cast<unsigned>((P.n + per - 1) / per), kTileThreads, LC_TILE_LDS, s, P);
     }
-    return hipGetLastError();
+    constexpr size_t per = 256 * waves * kTilesPerWave<false>;
+    return launch(tile_apply_kernel<IN, KOUT, false>, static_cast<unsigned>((P.n + per - 1) / per), kTileThreads, LC_TILE_LDS, s, P);
 }
 
 template <int IN, int GDT, bool APPLY, bool MOM, bool KOUT>
@@ -1016,8 +996,7 @@ static hipError_t launch_one(const AggParams &P, hipStream_t s)
 {
     const unsigned grid = static_cast<unsigned>((P.n + kAggBlock - 1) / kAggBlock);
     const unsigned lds = (IN == IN_BITS && P.W >= 32) ? LC_AGG_LDS : 0;
-    aggregate_kernel<IN, GDT, APPLY, MOM, KOUT><<<grid, kAggThreads, lds, s>>>(P);
-    return hipGetLastError();
+    return launch(aggregate_kernel<IN, GDT, APPLY, MOM, KOUT>, grid, kAggThreads, lds, s, P);
 }
 
 template <int IN, bool KOUT>

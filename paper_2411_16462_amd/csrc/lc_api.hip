@@ -40,15 +40,52 @@ int tie_code(int tie_rule, uint64_t step)
     return (step & 1u) ? 1 : 0;
 }
 
-// shared by the four aggregation entry points
-int aggregate(const void *q, const void *q2, size_t q_stride_bytes, int in_bits, int W, size_t n, int p, int levels, void *sum_out, uint64_t *vote_pos,
-              uint64_t *vote_nz, uint64_t step, int tie_rule, bool apply, float *theta, float lr, float wd, float *m,
-              size_t m_stride, const void *g, size_t g_stride, int g_dtype, int n_m, float beta2, void *stream,
-              const Groups &groups = Groups())
+// Segment ends are uint32 in units of 64 elements: a group table cannot describe more.
+constexpr size_t kMaxGroupedN = static_cast<size_t>(64) * 0xFFFFFFFFull;
+
+// One aggregation call, filled in by name by its entry point (whatever an entry point does
+// not have keeps the default: no second plane buffer, no sum, no planes out, nothing
+// applied, no momentum rows, no group table).
+struct AggCall {
+    const void *q = nullptr;        // packed rows: 1-bit words, fields, or the pos rows of the ternary format
+    const void *q2 = nullptr;       // ternary format: the nz rows
+    size_t q_stride_bytes = 0;
+    int in_bits = 1;                // 1, 2 / 4 / 8 (fields), 16 (ternary)
+    int W = 0;
+    size_t n = 0;
+    int p = 0;                      // p-bit sum: range rule W <= 2^p - 1; 0 = not a p-bit sum
+    int levels = 0;                 // summed level bytes: L; 0 = not a level sum
+    void *sum_out = nullptr;
+    uint64_t *vote_pos = nullptr;
+    uint64_t *vote_nz = nullptr;
+    uint64_t step = 1;
+    int tie_rule = LC_TIE_ZERO;
+    bool apply = false;
+    float *theta = nullptr;
+    float lr = 0.0f, wd = 0.0f;
+    float *m = nullptr;
+    size_t m_stride = 0;
+    const void *g = nullptr;
+    size_t g_stride = 0;
+    int g_dtype = LC_F32;
+    int n_m = 0;
+    float beta2 = 0.0f;
+    bool grouped = false;           // a *_groups entry point: the table below is required
+    Groups groups;
+    void *stream = nullptr;
+};
+
+// shared by the aggregation entry points
+int aggregate(const AggCall &c)
 {
-    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N) return LC_ERR_SIZE;
-    if (groups.n < 0 || (groups.n > 0 && (!groups.end64 || !groups.lr || !groups.wd))) return groups.n < 0 ? LC_ERR_SIZE : LC_ERR_NULL;
-    if (tie_rule != LC_TIE_ZERO && tie_rule != LC_TIE_ALT) return LC_ERR_MODE;
+    const int W = c.W, p = c.p, levels = c.levels, in_bits = c.in_bits;
+    if (W < 1 || W > LC_MAX_W || c.n > LC_MAX_N) return LC_ERR_SIZE;
+    if (c.grouped) {
+        if (c.groups.n < 1 || c.groups.n > LC_MAX_GROUPS || c.n > kMaxGroupedN) return LC_ERR_SIZE;
+        if (!c.groups.end64 || !c.groups.lr || !c.groups.wd) return LC_ERR_NULL;
+        if (!aligned(c.groups.end64, 4) || !aligned(c.groups.lr, 4) || !aligned(c.groups.wd, 4)) return LC_ERR_ALIGN;
+    }
+    if (c.tie_rule != LC_TIE_ZERO && c.tie_rule != LC_TIE_ALT) return LC_ERR_MODE;
     int sum_bits = 0;
     if (levels != 0) {  // summed level bytes: every row holds level + L in [0, 2L]
         if (levels < 1 || levels > 127 || 2 * levels * W > 255) return LC_ERR_RANGE;
@@ -61,55 +98,76 @@ int aggregate(const void *q, const void *q2, size_t q_stride_bytes, int in_bits,
     } else if (in_bits != 1 && in_bits != 16) {
         return LC_ERR_MODE;
     }
-    if (!q || (in_bits == 16 && !q2)) return LC_ERR_NULL;
-    if (in_bits == 16 && !aligned(q2, 8)) return LC_ERR_ALIGN;
+    if (!c.q || (in_bits == 16 && !c.q2)) return LC_ERR_NULL;
+    if (in_bits == 16 && !aligned(c.q2, 8)) return LC_ERR_ALIGN;
     if (in_bits == 1 || in_bits == 16) {
-        if (!aligned(q, 8) || (W > 1 && q_stride_bytes % 8 != 0)) return LC_ERR_ALIGN;
+        if (!aligned(c.q, 8) || (W > 1 && c.q_stride_bytes % 8 != 0)) return LC_ERR_ALIGN;
     } else {
-        if (!aligned(q, 16) || (W > 1 && q_stride_bytes % 16 != 0)) return LC_ERR_ALIGN;
+        if (!aligned(c.q, 16) || (W > 1 && c.q_stride_bytes % 16 != 0)) return LC_ERR_ALIGN;
     }
-    if (sum_out && !aligned(sum_out, 16)) return LC_ERR_ALIGN;
-    if (!aligned(vote_pos, 8) || !aligned(vote_nz, 8)) return LC_ERR_ALIGN;
-    if (apply) {
-        if (!theta) return LC_ERR_NULL;
-        if (!aligned(theta, 16)) return LC_ERR_ALIGN;
-        if (n_m < 0 || n_m > LC_MAX_W) return LC_ERR_SIZE;
-        if (n_m > 0) {
-            const int rc = check_mg(m, m_stride, g, g_stride, g_dtype, n_m);
+    if (c.sum_out && !aligned(c.sum_out, 16)) return LC_ERR_ALIGN;
+    if (!aligned(c.vote_pos, 8) || !aligned(c.vote_nz, 8)) return LC_ERR_ALIGN;
+    if (c.apply) {
+        if (!c.theta) return LC_ERR_NULL;
+        if (!aligned(c.theta, 16)) return LC_ERR_ALIGN;
+        if (c.n_m < 0 || c.n_m > LC_MAX_W) return LC_ERR_SIZE;
+        if (c.n_m > 0) {
+            const int rc = check_mg(c.m, c.m_stride, c.g, c.g_stride, c.g_dtype, c.n_m);
             if (rc) return rc;
         }
     }
-    if (n == 0) return LC_OK;
+    if (c.n == 0) return LC_OK;
     AggParams P{};
-    P.q = q;
-    P.q2 = q2;
-    P.q_stride_bytes = q_stride_bytes;
+    P.q = c.q;
+    P.q2 = c.q2;
+    P.q_stride_bytes = c.q_stride_bytes;
     P.W = W;
-    P.n = n;
+    P.n = c.n;
     P.sum_bits = sum_bits;
-    P.sum_out = sum_out;
-    P.vote_pos = vote_pos;
-    P.vote_nz = vote_nz;
-    P.tie = tie_code(tie_rule, step);
+    P.sum_out = c.sum_out;
+    P.vote_pos = c.vote_pos;
+    P.vote_nz = c.vote_nz;
+    P.tie = tie_code(c.tie_rule, c.step);
     P.thresh = levels > 0 ? W * levels : (W >> 1);
     P.tie_possible = levels > 0 ? 1 : ((W & 1) == 0);
-    P.theta = theta;
-    P.lr = lr;
-    P.wd = wd;
-    P.seg_end64 = groups.end64;
-    P.seg_lr = groups.lr;
-    P.seg_wd = groups.wd;
-    P.n_seg = groups.n;
-    P.m = m;
-    P.m_stride = m_stride;
-    P.g = g;
-    P.g_stride = g_stride;
-    P.n_m = apply ? n_m : 0;
-    P.beta2 = beta2;
-    P.omb2 = 1.0f - beta2;
-    const bool kout = in_bits == 1 && sum_out != nullptr;
-    return from_hip(launch_aggregate(P, in_bits, apply, kout, (apply && n_m > 0) ? g_dtype : LC_F32,
-                                     static_cast<hipStream_t>(stream)));
+    P.theta = c.theta;
+    P.lr = c.lr;
+    P.wd = c.wd;
+    P.seg_end64 = c.groups.end64;
+    P.seg_lr = c.groups.lr;
+    P.seg_wd = c.groups.wd;
+    P.n_seg = c.grouped ? c.groups.n : 0;
+    P.m = c.m;
+    P.m_stride = c.m_stride;
+    P.g = c.g;
+    P.g_stride = c.g_stride;
+    P.n_m = c.apply ? c.n_m : 0;
+    P.beta2 = c.beta2;
+    P.omb2 = 1.0f - c.beta2;
+    const bool kout = in_bits == 1 && c.sum_out != nullptr;
+    return from_hip(launch_aggregate(P, in_bits, c.apply, kout, (c.apply && c.n_m > 0) ? c.g_dtype : LC_F32,
+                                     static_cast<hipStream_t>(c.stream)));
+}
+
+// the momentum / gradient rows of an apply call
+void set_streams(AggCall &c, float *m, size_t m_stride, const void *g, size_t g_stride, int g_dtype, int n_m, float beta2)
+{
+    c.m = m;
+    c.m_stride = m_stride;
+    c.g = g;
+    c.g_stride = g_stride;
+    c.g_dtype = g_dtype;
+    c.n_m = n_m;
+    c.beta2 = beta2;
+}
+
+void set_groups(AggCall &c, const uint32_t *end64, const float *lr, const float *wd, int n_groups)
+{
+    c.grouped = true;
+    c.groups.end64 = end64;
+    c.groups.lr = lr;
+    c.groups.wd = wd;
+    c.groups.n = n_groups;
 }
 
 }  // namespace
@@ -142,24 +200,59 @@ int lc_local_update_pack(const void *g, size_t g_stride_elems, int g_dtype, floa
 int lc_vote_1bit(const uint64_t *q, size_t q_stride_words, int W, size_t n, uint64_t *vote_pos, uint64_t *vote_nz,
                  uint64_t step, int tie_rule, void *stream)
 {
-    return aggregate(q, nullptr, q_stride_words * 8, 1, W, n, 0, 0, nullptr, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f, 0.0f,
-                     nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream);
+    AggCall c;
+    c.q = q;
+    c.q_stride_bytes = q_stride_words * 8;
+    c.in_bits = 1;
+    c.W = W;
+    c.n = n;
+    c.vote_pos = vote_pos;
+    c.vote_nz = vote_nz;
+    c.step = step;
+    c.tie_rule = tie_rule;
+    c.stream = stream;
+    return aggregate(c);
 }
 
 int lc_pbit_sum_sign(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n, int p, void *sum_out,
                      uint64_t *vote_pos, uint64_t *vote_nz, uint64_t step, int tie_rule, void *stream)
 {
     if (p == 0) return LC_ERR_RANGE;
-    return aggregate(q, nullptr, q_stride_bytes, in_bits, W, n, p, 0, sum_out, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f,
-                     0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream);
+    AggCall c;
+    c.q = q;
+    c.q_stride_bytes = q_stride_bytes;
+    c.in_bits = in_bits;
+    c.W = W;
+    c.n = n;
+    c.p = p;
+    c.sum_out = sum_out;
+    c.vote_pos = vote_pos;
+    c.vote_nz = vote_nz;
+    c.step = step;
+    c.tie_rule = tie_rule;
+    c.stream = stream;
+    return aggregate(c);
 }
 
 int lc_vote_apply_1bit(const uint64_t *q, size_t q_stride_words, int W, size_t n, uint64_t step, int tie_rule, float *theta,
                        float lr, float wd, float *m, size_t m_stride_elems, const void *g, size_t g_stride_elems, int g_dtype,
                        int n_m, float beta2, void *stream)
 {
-    return aggregate(q, nullptr, q_stride_words * 8, 1, W, n, 0, 0, nullptr, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
-                     m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
+    AggCall c;
+    c.q = q;
+    c.q_stride_bytes = q_stride_words * 8;
+    c.in_bits = 1;
+    c.W = W;
+    c.n = n;
+    c.step = step;
+    c.tie_rule = tie_rule;
+    c.apply = true;
+    c.theta = theta;
+    c.lr = lr;
+    c.wd = wd;
+    set_streams(c, m, m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2);
+    c.stream = stream;
+    return aggregate(c);
 }
 
 int lc_pbit_sum_apply(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n, int p, void *sum_out, uint64_t step,
@@ -167,8 +260,23 @@ int lc_pbit_sum_apply(const void *q, size_t q_stride_bytes, int in_bits, int W, 
                       size_t g_stride_elems, int g_dtype, int n_m, float beta2, void *stream)
 {
     if (p == 0) return LC_ERR_RANGE;
-    return aggregate(q, nullptr, q_stride_bytes, in_bits, W, n, p, 0, sum_out, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
-                     m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
+    AggCall c;
+    c.q = q;
+    c.q_stride_bytes = q_stride_bytes;
+    c.in_bits = in_bits;
+    c.W = W;
+    c.n = n;
+    c.p = p;
+    c.sum_out = sum_out;
+    c.step = step;
+    c.tie_rule = tie_rule;
+    c.apply = true;
+    c.theta = theta;
+    c.lr = lr;
+    c.wd = wd;
+    set_streams(c, m, m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2);
+    c.stream = stream;
+    return aggregate(c);
 }
 
 int lc_apply_update(float *theta, const uint64_t *vote_pos, const uint64_t *vote_nz, size_t n, float lr, float wd, float *m,
@@ -284,7 +392,7 @@ int lc_l1_mean_abs_groups(const void *g, size_t g_stride_elems, int g_dtype, con
                           size_t n, float beta1, const uint32_t *group_end64, const uint64_t *group_count, int n_groups,
                           double *mean_abs, uint64_t *workspace, void *stream)
 {
-    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N || n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
+    if (W < 1 || W > LC_MAX_W || n > kMaxGroupedN || n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
     const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
     if (rc) return rc;
     if (!mean_abs || !workspace || !group_end64) return LC_ERR_NULL;
@@ -317,7 +425,7 @@ int lc_l1_quantize_pack_groups(const void *g, size_t g_stride_elems, int g_dtype
                                size_t n, float beta1, int update_m, float beta2, int levels, const uint32_t *group_end64,
                                int n_groups, const double *mean_abs, uint8_t *q, size_t q_stride_bytes, void *stream)
 {
-    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N || n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
+    if (W < 1 || W > LC_MAX_W || n > kMaxGroupedN || n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
     if (levels < 1 || levels > 127) return LC_ERR_RANGE;
     const int rc = check_mg(m, m_stride_elems, g, g_stride_elems, g_dtype, W);
     if (rc) return rc;
@@ -336,8 +444,20 @@ int lc_level_sum_sign(const uint8_t *q, size_t q_stride_bytes, int W, size_t n, 
                       uint64_t *vote_pos, uint64_t *vote_nz, uint64_t step, int tie_rule, void *stream)
 {
     if (levels == 0) return LC_ERR_RANGE;
-    return aggregate(q, nullptr, q_stride_bytes, 8, W, n, 0, levels, sum_out, vote_pos, vote_nz, step, tie_rule, false, nullptr, 0.0f,
-                     0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream);
+    AggCall c;
+    c.q = q;
+    c.q_stride_bytes = q_stride_bytes;
+    c.in_bits = 8;
+    c.W = W;
+    c.n = n;
+    c.levels = levels;
+    c.sum_out = sum_out;
+    c.vote_pos = vote_pos;
+    c.vote_nz = vote_nz;
+    c.step = step;
+    c.tie_rule = tie_rule;
+    c.stream = stream;
+    return aggregate(c);
 }
 
 int lc_level_sum_apply(const uint8_t *q, size_t q_stride_bytes, int W, size_t n, int levels, uint8_t *sum_out, uint64_t step,
@@ -345,8 +465,23 @@ int lc_level_sum_apply(const uint8_t *q, size_t q_stride_bytes, int W, size_t n,
                        size_t g_stride_elems, int g_dtype, int n_m, float beta2, void *stream)
 {
     if (levels == 0) return LC_ERR_RANGE;
-    return aggregate(q, nullptr, q_stride_bytes, 8, W, n, 0, levels, sum_out, nullptr, nullptr, step, tie_rule, true, theta, lr, wd, m,
-                     m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
+    AggCall c;
+    c.q = q;
+    c.q_stride_bytes = q_stride_bytes;
+    c.in_bits = 8;
+    c.W = W;
+    c.n = n;
+    c.levels = levels;
+    c.sum_out = sum_out;
+    c.step = step;
+    c.tie_rule = tie_rule;
+    c.apply = true;
+    c.theta = theta;
+    c.lr = lr;
+    c.wd = wd;
+    set_streams(c, m, m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2);
+    c.stream = stream;
+    return aggregate(c);
 }
 
 int lc_level_sum_apply_groups(const uint8_t *q, size_t q_stride_bytes, int W, size_t n, int levels, uint8_t *sum_out,
@@ -354,14 +489,21 @@ int lc_level_sum_apply_groups(const uint8_t *q, size_t q_stride_bytes, int W, si
                               const float *group_wd, int n_groups, void *stream)
 {
     if (levels == 0) return LC_ERR_RANGE;
-    if (n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
-    Groups grp;
-    grp.end64 = group_end64;
-    grp.lr = group_lr;
-    grp.wd = group_wd;
-    grp.n = n_groups;
-    return aggregate(q, nullptr, q_stride_bytes, 8, W, n, 0, levels, sum_out, nullptr, nullptr, step, tie_rule, true, theta, 0.0f,
-                     0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream, grp);
+    AggCall c;
+    c.q = q;
+    c.q_stride_bytes = q_stride_bytes;
+    c.in_bits = 8;
+    c.W = W;
+    c.n = n;
+    c.levels = levels;
+    c.sum_out = sum_out;
+    c.step = step;
+    c.tie_rule = tie_rule;
+    c.apply = true;
+    c.theta = theta;
+    set_groups(c, group_end64, group_lr, group_wd, n_groups);
+    c.stream = stream;
+    return aggregate(c);
 }
 
 int lc_local_update_pack_ternary(const void *g, size_t g_stride_elems, int g_dtype, float *m, size_t m_stride_elems, int W,
@@ -382,16 +524,37 @@ int lc_local_update_pack_ternary(const void *g, size_t g_stride_elems, int g_dty
 int lc_vote_ternary(const uint64_t *pos, const uint64_t *nz, size_t q_stride_words, int W, size_t n, uint64_t *vote_pos,
                     uint64_t *vote_nz, void *stream)
 {
-    return aggregate(pos, nz, q_stride_words * 8, 16, W, n, 0, 0, nullptr, vote_pos, vote_nz, 1, LC_TIE_ZERO, false, nullptr,
-                     0.0f, 0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream);
+    AggCall c;
+    c.q = pos;
+    c.q2 = nz;
+    c.q_stride_bytes = q_stride_words * 8;
+    c.in_bits = 16;
+    c.W = W;
+    c.n = n;
+    c.vote_pos = vote_pos;
+    c.vote_nz = vote_nz;
+    c.stream = stream;
+    return aggregate(c);
 }
 
 int lc_vote_apply_ternary(const uint64_t *pos, const uint64_t *nz, size_t q_stride_words, int W, size_t n, float *theta,
                           float lr, float wd, float *m, size_t m_stride_elems, const void *g, size_t g_stride_elems,
                           int g_dtype, int n_m, float beta2, void *stream)
 {
-    return aggregate(pos, nz, q_stride_words * 8, 16, W, n, 0, 0, nullptr, nullptr, nullptr, 1, LC_TIE_ZERO, true, theta, lr,
-                     wd, m, m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2, stream);
+    AggCall c;
+    c.q = pos;
+    c.q2 = nz;
+    c.q_stride_bytes = q_stride_words * 8;
+    c.in_bits = 16;
+    c.W = W;
+    c.n = n;
+    c.apply = true;
+    c.theta = theta;
+    c.lr = lr;
+    c.wd = wd;
+    set_streams(c, m, m_stride_elems, g, g_stride_elems, g_dtype, n_m, beta2);
+    c.stream = stream;
+    return aggregate(c);
 }
 
 int lc_momentum_divergence(const float *m, size_t m_stride_elems, int W, size_t n, double *max_std, void *stream)
@@ -405,7 +568,7 @@ int lc_momentum_divergence(const float *m, size_t m_stride_elems, int W, size_t 
 int lc_momentum_divergence_groups(const float *m, size_t m_stride_elems, int W, size_t n, const uint32_t *group_end64,
                                   int n_groups, double *max_std, void *stream)
 {
-    if (W < 1 || W > LC_MAX_W || n > LC_MAX_N || n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
+    if (W < 1 || W > LC_MAX_W || n > kMaxGroupedN || n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
     if (!m || !max_std || !group_end64) return LC_ERR_NULL;
     if (!aligned(m, 16) || (W > 1 && (m_stride_elems * 4) % 16 != 0) || !aligned(max_std, 8) || !aligned(group_end64, 4))
         return LC_ERR_ALIGN;
@@ -437,14 +600,19 @@ int lc_vote_apply_1bit_groups(const uint64_t *q, size_t q_stride_words, int W, s
                               float *theta, const uint32_t *group_end64, const float *group_lr, const float *group_wd,
                               int n_groups, void *stream)
 {
-    if (n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
-    Groups gr;
-    gr.end64 = group_end64;
-    gr.lr = group_lr;
-    gr.wd = group_wd;
-    gr.n = n_groups;
-    return aggregate(q, nullptr, q_stride_words * 8, 1, W, n, 0, 0, nullptr, nullptr, nullptr, step, tie_rule, true, theta,
-                     0.0f, 0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream, gr);
+    AggCall c;
+    c.q = q;
+    c.q_stride_bytes = q_stride_words * 8;
+    c.in_bits = 1;
+    c.W = W;
+    c.n = n;
+    c.step = step;
+    c.tie_rule = tie_rule;
+    c.apply = true;
+    c.theta = theta;
+    set_groups(c, group_end64, group_lr, group_wd, n_groups);
+    c.stream = stream;
+    return aggregate(c);
 }
 
 int lc_pbit_sum_apply_groups(const void *q, size_t q_stride_bytes, int in_bits, int W, size_t n, int p, void *sum_out,
@@ -452,28 +620,39 @@ int lc_pbit_sum_apply_groups(const void *q, size_t q_stride_bytes, int in_bits, 
                              const float *group_wd, int n_groups, void *stream)
 {
     if (p == 0) return LC_ERR_RANGE;
-    if (n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
-    Groups gr;
-    gr.end64 = group_end64;
-    gr.lr = group_lr;
-    gr.wd = group_wd;
-    gr.n = n_groups;
-    return aggregate(q, nullptr, q_stride_bytes, in_bits, W, n, p, 0, sum_out, nullptr, nullptr, step, tie_rule, true, theta,
-                     0.0f, 0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream, gr);
+    AggCall c;
+    c.q = q;
+    c.q_stride_bytes = q_stride_bytes;
+    c.in_bits = in_bits;
+    c.W = W;
+    c.n = n;
+    c.p = p;
+    c.sum_out = sum_out;
+    c.step = step;
+    c.tie_rule = tie_rule;
+    c.apply = true;
+    c.theta = theta;
+    set_groups(c, group_end64, group_lr, group_wd, n_groups);
+    c.stream = stream;
+    return aggregate(c);
 }
 
 int lc_vote_apply_ternary_groups(const uint64_t *pos, const uint64_t *nz, size_t q_stride_words, int W, size_t n,
                                  float *theta, const uint32_t *group_end64, const float *group_lr, const float *group_wd,
                                  int n_groups, void *stream)
 {
-    if (n_groups < 1 || n_groups > LC_MAX_GROUPS) return LC_ERR_SIZE;
-    Groups gr;
-    gr.end64 = group_end64;
-    gr.lr = group_lr;
-    gr.wd = group_wd;
-    gr.n = n_groups;
-    return aggregate(pos, nz, q_stride_words * 8, 16, W, n, 0, 0, nullptr, nullptr, nullptr, 1, LC_TIE_ZERO, true, theta, 0.0f,
-                     0.0f, nullptr, 0, nullptr, 0, LC_F32, 0, 0.0f, stream, gr);
+    AggCall c;
+    c.q = pos;
+    c.q2 = nz;
+    c.q_stride_bytes = q_stride_words * 8;
+    c.in_bits = 16;
+    c.W = W;
+    c.n = n;
+    c.apply = true;
+    c.theta = theta;
+    set_groups(c, group_end64, group_lr, group_wd, n_groups);
+    c.stream = stream;
+    return aggregate(c);
 }
 
 int lc_container_bits(int p) { return container(p); }

@@ -135,6 +135,41 @@ __device__ __forceinline__ size_t xcd_chunk_index(unsigned b, unsigned nblocks)
     return b;
 }
 
+// Group tables (per-tensor rates, scales, divergences): G consecutive segments of the range,
+// segment s ending at element 64 * end64[s], ends ascending.  One rule in every kernel: a
+// 64-element block b belongs to the first segment whose end lies beyond it, and to the last
+// segment if there is none (a last end short of n stretches to n; ends beyond n mean n).
+// group_find bisects (uniform when b is); group_walk moves on from a segment at or before
+// the right one, for lanes whose block lies a little further on.
+__device__ __forceinline__ int group_find(const uint32_t *end64, int G, uint32_t b)
+{
+    int lo = 0, hi = G - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (end64[mid] > b) hi = mid;
+        else lo = mid + 1;
+    }
+    return lo;
+}
+__device__ __forceinline__ int group_walk(const uint32_t *end64, int G, int s, uint32_t b)
+{
+    while (s < G - 1 && b >= end64[s]) ++s;
+    return s;
+}
+// the blocks [lo, hi) of segment s under the same rule (n64 = blocks in the range)
+__device__ __forceinline__ uint32_t group_lo64(const uint32_t *end64, int s, uint32_t n64)
+{
+    if (s == 0) return 0u;
+    const uint32_t v = end64[s - 1];
+    return v < n64 ? v : n64;
+}
+__device__ __forceinline__ uint32_t group_hi64(const uint32_t *end64, int G, int s, uint32_t n64)
+{
+    const uint32_t v = s == G - 1 ? n64 : end64[s];
+    const uint32_t hi = v < n64 ? v : n64, lo = group_lo64(end64, s, n64);
+    return hi > lo ? hi : lo;
+}
+
 // Algorithm 1 line 6 in fp32: one rounded product, one fused multiply-add.
 __device__ __forceinline__ float momentum_step(float m, float g, float beta2, float omb2)
 {

@@ -108,21 +108,6 @@ __global__ void l1_zero_kernel(uint64_t *workspace, size_t words)
     if (i < words) workspace[i] = 0;
 }
 
-// Segment s of a group table covers the 64-element blocks [seg_lo64, seg_hi64); ends beyond
-// the arena are clamped, ends that do not ascend give an empty segment.
-__device__ __forceinline__ uint32_t seg_lo64(const uint32_t *end64, int s, uint32_t n64)
-{
-    if (s == 0) return 0u;
-    const uint32_t v = end64[s - 1];
-    return v < n64 ? v : n64;
-}
-__device__ __forceinline__ uint32_t seg_hi64(const uint32_t *end64, int s, uint32_t n64)
-{
-    const uint32_t v = end64[s];
-    const uint32_t hi = v < n64 ? v : n64, lo = seg_lo64(end64, s, n64);
-    return hi > lo ? hi : lo;
-}
-
 // plan[s] = number of summing workgroups of the groups before s, plan[G] = their total.
 // One workgroup: each thread adds a contiguous share of the groups, thread 0 scans the
 // shares.
@@ -135,7 +120,7 @@ __global__ __launch_bounds__(256) void l1_plan_kernel(const uint32_t *__restrict
     const int lo = static_cast<int>(threadIdx.x) * per;
     const int hi = lo + per < G ? lo + per : G;
     uint32_t sum = 0;
-    for (int s = lo; s < hi; ++s) sum += (seg_hi64(end64, s, n64) - seg_lo64(end64, s, n64) + kL1Block64 - 1) / kL1Block64;
+    for (int s = lo; s < hi; ++s) sum += (group_hi64(end64, G, s, n64) - group_lo64(end64, s, n64) + kL1Block64 - 1) / kL1Block64;
     part[threadIdx.x] = sum;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -151,7 +136,7 @@ __global__ __launch_bounds__(256) void l1_plan_kernel(const uint32_t *__restrict
     uint32_t run = part[threadIdx.x];
     for (int s = lo; s < hi; ++s) {
         plan[s] = run;
-        run += (seg_hi64(end64, s, n64) - seg_lo64(end64, s, n64) + kL1Block64 - 1) / kL1Block64;
+        run += (group_hi64(end64, G, s, n64) - group_lo64(end64, s, n64) + kL1Block64 - 1) / kL1Block64;
     }
 }
 
@@ -185,8 +170,8 @@ __global__ __launch_bounds__(kL1Threads) void l1_abs_sum_kernel(const void *__re
             else hi = mid;
         }
         const uint32_t n64 = static_cast<uint32_t>((n_all + 63) / 64);
-        first = static_cast<size_t>(seg_lo64(end64, lo, n64)) * 64;
-        const size_t last = static_cast<size_t>(seg_hi64(end64, lo, n64)) * 64;
+        first = static_cast<size_t>(group_lo64(end64, lo, n64)) * 64;
+        const size_t last = static_cast<size_t>(group_hi64(end64, G, lo, n64)) * 64;
         n = last < n_all ? last : n_all;
         local_block = blockIdx.x - plan[lo];
         acc = w * static_cast<size_t>(G) + static_cast<size_t>(lo);
@@ -288,8 +273,8 @@ __global__ void l1_finalize_kernel(uint64_t *workspace, int n_acc, size_t n_all,
             n = count[s];
         } else {
             const uint32_t n64 = static_cast<uint32_t>((n_all + 63) / 64);
-            const size_t lo = static_cast<size_t>(seg_lo64(end64, s, n64)) * 64;
-            size_t hi = static_cast<size_t>(seg_hi64(end64, s, n64)) * 64;
+            const size_t lo = static_cast<size_t>(group_lo64(end64, s, n64)) * 64;
+            size_t hi = static_cast<size_t>(group_hi64(end64, G, s, n64)) * 64;
             hi = hi < n_all ? hi : n_all;
             n = hi - lo;
         }
@@ -340,30 +325,27 @@ hipError_t launch_l1_mean_abs(const void *g, size_t g_stride, int g_dtype, const
     const size_t n_acc = static_cast<size_t>(W) * static_cast<size_t>(G > 0 ? G : 1);
     const size_t words = n_acc * kL1Slots * kL1Limbs;
     uint32_t *plan = reinterpret_cast<uint32_t *>(workspace + words);
-    l1_zero_kernel<<<static_cast<unsigned>((words + 255) / 256), 256, 0, s>>>(workspace, words);
+    hipError_t e = launch(l1_zero_kernel, static_cast<unsigned>((words + 255) / 256), 256, 0, s, workspace, words);
+    if (e != hipSuccess) return e;
     if (n > 0) {
         const float omb1 = 1.0f - beta1;
         size_t blocks = (n + kL1Block - 1) / kL1Block;
         if (G > 0) {
             blocks += static_cast<size_t>(G);  // every group may end in a partly filled workgroup
-            l1_plan_kernel<<<1, 256, 0, s>>>(grp.end64, G, static_cast<uint32_t>((n + 63) / 64), plan);
+            e = launch(l1_plan_kernel, 1, 256, 0, s, grp.end64, G, static_cast<uint32_t>((n + 63) / 64), plan);
+            if (e != hipSuccess) return e;
         }
         const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>(W));
-#define LC_LAUNCH(GDT, GROUPED)                                                                                        \
-    l1_abs_sum_kernel<GDT, GROUPED><<<grid, kL1Threads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, workspace, \
-                                                                grp.end64, plan, G)
-        if (g_dtype == LC_BF16) {
-            if (G > 0) LC_LAUNCH(LC_BF16, true);
-            else LC_LAUNCH(LC_BF16, false);
-        } else {
-            if (G > 0) LC_LAUNCH(LC_F32, true);
-            else LC_LAUNCH(LC_F32, false);
-        }
+#define LC_LAUNCH(GDT, GROUPED)                                                                                      \
+    launch(l1_abs_sum_kernel<GDT, GROUPED>, grid, kL1Threads, 0, s, g, g_stride, m, m_stride, n, beta1, omb1, workspace, \
+           grp.end64, static_cast<const uint32_t *>(plan), G)
+        if (g_dtype == LC_BF16) e = G > 0 ? LC_LAUNCH(LC_BF16, true) : LC_LAUNCH(LC_BF16, false);
+        else e = G > 0 ? LC_LAUNCH(LC_F32, true) : LC_LAUNCH(LC_F32, false);
 #undef LC_LAUNCH
+        if (e != hipSuccess) return e;
     }
-    l1_finalize_kernel<<<static_cast<unsigned>((n_acc + 63) / 64), 64, 0, s>>>(workspace, static_cast<int>(n_acc), n, mean_abs,
-                                                                               grp.end64, grp.count, G);
-    return hipGetLastError();
+    return launch(l1_finalize_kernel, static_cast<unsigned>((n_acc + 63) / 64), 64, 0, s, workspace, static_cast<int>(n_acc), n,
+                  mean_abs, grp.end64, grp.count, G);
 }
 
 // ---- pass 1 for callers that cannot allocate -------------------------------------------
@@ -450,16 +432,9 @@ __global__ __launch_bounds__(kQuantThreads) void l1_quantize_pack_kernel(const v
     if (GROUPED) {
         // first group that ends beyond the tile's first 64-element block (uniform), then
         // each lane walks on to the group of its own block
-        const uint32_t t64 = static_cast<uint32_t>(tile / 64);
-        int lo = 0, hi = G - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (end64[mid] > t64) hi = mid;
-            else lo = mid + 1;
-        }
-        const uint32_t e64 = static_cast<uint32_t>(e / 64);
-        while (lo < G - 1 && e64 >= end64[lo]) ++lo;
-        mean_index = w * static_cast<size_t>(G) + static_cast<size_t>(lo);
+        const int first = group_find(end64, G, static_cast<uint32_t>(tile / 64));
+        const int sgm = group_walk(end64, G, first, static_cast<uint32_t>(e / 64));
+        mean_index = w * static_cast<size_t>(G) + static_cast<size_t>(sgm);
     }
     const double mean = mean_abs[mean_index];
     const bool live = mean > 0.0;                       // all-zero input: every level is 0
@@ -492,23 +467,20 @@ hipError_t launch_l1_quantize_pack(const void *g, size_t g_stride, int g_dtype, 
 {
     const dim3 grid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(W));
     const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
-#define LC_LAUNCH(GDT, UPD, GRP)                                                                                        \
-    l1_quantize_pack_kernel<GDT, UPD, GRP><<<grid, kQuantThreads, 0, s>>>(g, g_stride, m, m_stride, n, beta1, omb1,    \
-                                                                          beta2, omb2, levels, mean_abs, q,            \
-                                                                          q_stride_bytes, grp.end64, grp.n)
-#define LC_LAUNCH2(GDT, UPD)             \
+#define LC_LAUNCH(GDT, UPD, GRP)                                                                                     \
+    return launch(l1_quantize_pack_kernel<GDT, UPD, GRP>, grid, kQuantThreads, 0, s, g, g_stride, m, m_stride, n, beta1, omb1, \
+                  beta2, omb2, levels, mean_abs, q, q_stride_bytes, grp.end64, grp.n)
+#define LC_LAUNCH2(GDT, UPD)                  \
     if (grp.n > 0) LC_LAUNCH(GDT, UPD, true); \
-    else LC_LAUNCH(GDT, UPD, false)
+    LC_LAUNCH(GDT, UPD, false)
     if (g_dtype == LC_BF16) {
         if (update_m) { LC_LAUNCH2(LC_BF16, true); }
-        else { LC_LAUNCH2(LC_BF16, false); }
-    } else {
-        if (update_m) { LC_LAUNCH2(LC_F32, true); }
-        else { LC_LAUNCH2(LC_F32, false); }
+        LC_LAUNCH2(LC_BF16, false);
     }
+    if (update_m) { LC_LAUNCH2(LC_F32, true); }
+    LC_LAUNCH2(LC_F32, false);
 #undef LC_LAUNCH2
 #undef LC_LAUNCH
-    return hipGetLastError();
 }
 
 }  // namespace lc

@@ -4,7 +4,29 @@
 
 #include "lc_common.hpp"
 
+#include <tuple>
+#include <utility>
+
 namespace lc {
+
+// Kernel launch that reports what THIS launch returned.  The <<< >>> form leaves its status
+// in the runtime's per-thread "last error", which also holds -- and, once read, forgets --
+// whatever an unrelated earlier call of the host program left there; hipLaunchKernel's own
+// return value neither sees nor clears that.
+template <typename... KArgs, size_t... I, typename Tuple>
+inline hipError_t launch_impl(void (*kernel)(KArgs...), dim3 grid, dim3 block, unsigned lds, hipStream_t s, Tuple &vals,
+                              std::index_sequence<I...>)
+{
+    void *ptrs[] = {const_cast<void *>(static_cast<const void *>(&std::get<I>(vals)))...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, lds, s);
+}
+template <typename... KArgs, typename... Args>
+inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, unsigned lds, hipStream_t s, Args &&...args)
+{
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "one argument per kernel parameter");
+    std::tuple<std::remove_cv_t<KArgs>...> vals(static_cast<std::remove_cv_t<KArgs>>(std::forward<Args>(args))...);
+    return launch_impl(kernel, grid, block, lds, s, vals, std::index_sequence_for<KArgs...>());
+}
 
 struct AggParams {
     const void *q;          // packed rows (1-bit words or fields); unused for IN_PLANES

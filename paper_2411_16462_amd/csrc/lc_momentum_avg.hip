@@ -12,9 +12,6 @@
 namespace lc {
 
 constexpr int kAvgTile = 256;  // elements per workgroup
-#ifndef LC_AVG_R
-#define LC_AVG_R 8
-#endif
 // Unused dynamic LDS per 8-wave workgroup: with the 8 KiB of partial sums it lets three
 // workgroups (24 waves) share a compute unit's 160 KiB instead of four -- measured +3 %
 // (6.2 against 6.0 TB/s at 16 rows); two workgroups lose 12 %.
@@ -76,17 +73,9 @@ hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStre
 {
     const unsigned grid = static_cast<unsigned>((n + kAvgTile - 1) / kAvgTile);
     const float inv_w = 1.0f / static_cast<float>(W);
-    if (W >= 8 && LC_AVG_R == 16)
-        momentum_avg_kernel<16><<<grid, 16 * kWave, LC_AVG_LDS, s>>>(m, stride, W, n, inv_w);
-    else if (W >= 8 && LC_AVG_R == 4)
-        momentum_avg_kernel<4><<<grid, 4 * kWave, LC_AVG_LDS, s>>>(m, stride, W, n, inv_w);
-    else if (W >= 8)
-        momentum_avg_kernel<8><<<grid, 8 * kWave, LC_AVG_LDS, s>>>(m, stride, W, n, inv_w);
-    else if (W >= 4)
-        momentum_avg_kernel<4><<<grid, 4 * kWave, 0, s>>>(m, stride, W, n, inv_w);
-    else
-        momentum_avg_kernel<2><<<grid, 2 * kWave, 0, s>>>(m, stride, W, n, inv_w);
-    return hipGetLastError();
+    if (W >= 8) return launch(momentum_avg_kernel<8>, grid, 8 * kWave, LC_AVG_LDS, s, m, stride, W, n, inv_w);
+    if (W >= 4) return launch(momentum_avg_kernel<4>, grid, 4 * kWave, 0, s, m, stride, W, n, inv_w);
+    return launch(momentum_avg_kernel<2>, grid, 2 * kWave, 0, s, m, stride, W, n, inv_w);
 }
 
 // ---- divergence of the workers' momenta (Section 5.1, the quantity of Figure 6) --------
@@ -165,17 +154,9 @@ __global__ __launch_bounds__(256) void momentum_divergence_kernel(const float *_
         // segment of the wave's first 64-element block by bisection (uniform), then each
         // lane walks on to the segment of its own block; lanes past n stay with the last
         const size_t first = (static_cast<size_t>(blockIdx.x) * 256 + static_cast<size_t>(wave) * kWave) * 4;
-        const uint32_t t64 = static_cast<uint32_t>(first / 64);
-        int lo = 0, hi = G - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (end64[mid] > t64) hi = mid;
-            else lo = mid + 1;
-        }
-        int seg = lo;
+        int seg = group_find(end64, G, static_cast<uint32_t>(first / 64));
         if (e < n) {
-            const uint32_t e64 = static_cast<uint32_t>(e / 64);
-            while (seg < G - 1 && e64 >= end64[seg]) ++seg;
+            seg = group_walk(end64, G, seg, static_cast<uint32_t>(e / 64));
         } else {
             seg = G - 1;
         }
@@ -202,13 +183,11 @@ hipError_t launch_momentum_divergence(const float *m, size_t stride, int W, size
                                       int n_groups, hipStream_t s)
 {
     const int count = n_groups > 0 ? n_groups : 1;
-    divergence_zero_kernel<<<(count + 255) / 256, 256, 0, s>>>(out, count);
-    if (n > 0) {
-        const unsigned grid = static_cast<unsigned>((n + 1023) / 1024);
-        if (n_groups > 0) momentum_divergence_kernel<true><<<grid, 256, 0, s>>>(m, stride, W, n, out, end64, n_groups);
-        else momentum_divergence_kernel<false><<<grid, 256, 0, s>>>(m, stride, W, n, out, nullptr, 0);
-    }
-    return hipGetLastError();
+    hipError_t e = launch(divergence_zero_kernel, (count + 255) / 256, 256, 0, s, out, count);
+    if (e != hipSuccess || n == 0) return e;
+    const unsigned grid = static_cast<unsigned>((n + 1023) / 1024);
+    if (n_groups > 0) return launch(momentum_divergence_kernel<true>, grid, 256, 0, s, m, stride, W, n, out, end64, n_groups);
+    return launch(momentum_divergence_kernel<false>, grid, 256, 0, s, m, stride, W, n, out, static_cast<const uint32_t *>(nullptr), 0);
 }
 
 }  // namespace lc

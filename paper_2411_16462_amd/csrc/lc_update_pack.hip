@@ -245,18 +245,16 @@ hipError_t launch_local_update_pack_ternary(const void *g, size_t g_stride, int 
 {
     const dim3 grid(static_cast<unsigned>((n + kPackBlock - 1) / kPackBlock), static_cast<unsigned>(W));
     const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
-#define LC_LAUNCH(GDT, UPD)                                                                                              \
-    local_update_pack_ternary_kernel<GDT, UPD><<<grid, kPackThreads, LC_PACK_LDS, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, \
-                                                                             beta2, omb2, pos, nz, stride_words)
+#define LC_LAUNCH(GDT, UPD)                                                                                         \
+    return launch(local_update_pack_ternary_kernel<GDT, UPD>, grid, kPackThreads, LC_PACK_LDS, s, g, g_stride, m, m_stride, \
+                  n, beta1, omb1, beta2, omb2, pos, nz, stride_words)
     if (g_dtype == LC_BF16) {
         if (update_m) LC_LAUNCH(LC_BF16, true);
-        else LC_LAUNCH(LC_BF16, false);
-    } else {
-        if (update_m) LC_LAUNCH(LC_F32, true);
-        else LC_LAUNCH(LC_F32, false);
+        LC_LAUNCH(LC_BF16, false);
     }
+    if (update_m) LC_LAUNCH(LC_F32, true);
+    LC_LAUNCH(LC_F32, false);
 #undef LC_LAUNCH
-    return hipGetLastError();
 }
 
 template <int GDT, int OUT_BITS>
@@ -265,12 +263,10 @@ static hipError_t launch_pack(bool update_m, dim3 grid, hipStream_t s, const voi
                               size_t q_stride_bytes, int zero_bit)
 {
     if (update_m)
-        local_update_pack_kernel<GDT, OUT_BITS, true><<<grid, kPackThreads, LC_PACK_LDS, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, beta2,
-                                                                              omb2, q, q_stride_bytes, zero_bit);
-    else
-        local_update_pack_kernel<GDT, OUT_BITS, false><<<grid, kPackThreads, LC_PACK_LDS, s>>>(g, g_stride, m, m_stride, n, beta1, omb1, beta2,
-                                                                               omb2, q, q_stride_bytes, zero_bit);
-    return hipGetLastError();
+        return launch(local_update_pack_kernel<GDT, OUT_BITS, true>, grid, kPackThreads, LC_PACK_LDS, s, g, g_stride, m, m_stride, n,
+                      beta1, omb1, beta2, omb2, q, q_stride_bytes, zero_bit);
+    return launch(local_update_pack_kernel<GDT, OUT_BITS, false>, grid, kPackThreads, LC_PACK_LDS, s, g, g_stride, m, m_stride, n,
+                  beta1, omb1, beta2, omb2, q, q_stride_bytes, zero_bit);
 }
 
 template <int GDT>

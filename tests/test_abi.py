@@ -263,3 +263,45 @@ def test_count_apply_validation():
     assert lc.lc_count_apply(**{**a, "k_fields": A + 8}) == lc.LC_ERR_ALIGN
     assert lc.lc_count_apply(**{**a, "n_m": 1}) == lc.LC_ERR_NULL             # momentum rows need m and g
     assert lc.lc_count_apply(**{**a, "n": lc.LC_MAX_N + 1}) == lc.LC_ERR_SIZE
+
+
+def test_group_table_limits_and_signatures():
+    """*_groups calls: the element count must fit the 32-bit segment ends (64 * (2^32 - 1)),
+    and no grouped apply takes momentum rows -- its signature has no m / g / n_m at all, so
+    such a call cannot be expressed."""
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    grouped = re.findall(r"int (lc_\w+_groups)\s*\(([^;]*?)\);", text, flags=re.S)
+    assert len(grouped) >= 7
+    for name, params in grouped:
+        if "_apply_" in name:
+            assert not re.search(r"\bn_m\b|\*\s*m\b|\*\s*g\b|beta2", params), name
+    too_long = 64 * (2 ** 32 - 1) + 64
+    assert too_long <= lc.LC_MAX_N
+    v = dict(q=A, q_stride_words=1 << 33, W=4, n=too_long, step=1, tie_rule=lc.LC_TIE_ZERO, theta=A, group_end64=A,
+             group_lr=A, group_wd=A, n_groups=3, stream=0, check=False)
+    assert lc.lc_vote_apply_1bit_groups(**v) == lc.LC_ERR_SIZE
+    assert lc.lc_vote_apply_1bit_groups(**{**v, "n": 0}) == lc.LC_OK
+    assert lc.lc_vote_apply_1bit_groups(**{**v, "n": 0, "n_groups": 0}) == lc.LC_ERR_SIZE
+    assert lc.lc_vote_apply_1bit_groups(**{**v, "n": 0, "n_groups": lc.LC_MAX_GROUPS + 1}) == lc.LC_ERR_SIZE
+    assert lc.lc_vote_apply_1bit_groups(**{**v, "n": 0, "group_lr": None}) == lc.LC_ERR_NULL
+    assert lc.lc_vote_apply_1bit_groups(**{**v, "n": 0, "group_end64": A + 2}) == lc.LC_ERR_ALIGN
+    d = dict(m=A, m_stride_elems=1 << 40, W=2, n=too_long, group_end64=A, n_groups=3, max_std=A, stream=0, check=False)
+    assert lc.lc_momentum_divergence_groups(**d) == lc.LC_ERR_SIZE
+    g = dict(g=A, g_stride_elems=1 << 40, g_dtype=lc.LC_F32, m=A, m_stride_elems=1 << 40, W=2, n=too_long, beta1=0.9,
+             group_end64=A, group_count=None, n_groups=3, mean_abs=A, workspace=A, stream=0, check=False)
+    assert lc.lc_l1_mean_abs_groups(**g) == lc.LC_ERR_SIZE
+    qz = dict(g=A, g_stride_elems=1 << 40, g_dtype=lc.LC_F32, m=A, m_stride_elems=1 << 40, W=2, n=too_long, beta1=0.9,
+              update_m=1, beta2=0.99, levels=15, group_end64=A, n_groups=3, mean_abs=A, q=A, q_stride_bytes=1 << 40,
+              stream=0, check=False)
+    assert lc.lc_l1_quantize_pack_groups(**qz) == lc.LC_ERR_SIZE
+
+
+def test_static_workspace_entry_point_validation():
+    a = dict(g=A, g_stride_elems=1024, g_dtype=lc.LC_F32, m=A, m_stride_elems=1024, n=10, beta1=0.9, mean_abs=A,
+             stream=0, check=False)
+    assert lc.lc_l1_mean_abs_static(W=lc.LC_L1_STATIC_MAX_W + 1, **a) == lc.LC_ERR_SIZE
+    assert lc.lc_l1_mean_abs_static(W=0, **a) == lc.LC_ERR_SIZE
+    assert lc.lc_l1_mean_abs_static(W=2, **{**a, "mean_abs": None}) == lc.LC_ERR_NULL
+    assert lc.lc_l1_mean_abs_static(W=2, **{**a, "g_dtype": 7}) == lc.LC_ERR_DTYPE
+    text = open(HEADER).read()
+    assert int(re.search(r"#define LC_L1_STATIC_MAX_W (\d+)", text).group(1)) == lc.LC_L1_STATIC_MAX_W

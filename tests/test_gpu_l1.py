@@ -149,7 +149,9 @@ def segments_of(ends64, n):
     """[(lo, hi)] element ranges of a group table, as the C ABI defines them."""
     n64 = (n + 63) // 64
     out, prev = [], 0
-    for e in ends64:
+    for s, e in enumerate(ends64):
+        if s == len(ends64) - 1:
+            e = n64                       # the last segment reaches the end of the range whatever its end says
         lo = min(prev, n64)
         hi = max(min(e, n64), lo)
         out.append((lo * 64, min(hi * 64, n)))
@@ -285,6 +287,34 @@ def test_l1_groups_gpt2_small_table():
     case.snapshot()
     out = run_l1_groups(case, L, 2, ends64)
     check_l1_groups(case, out, L, 2, ends64)
+
+
+@pytest.mark.parametrize("last", [300, 5000])
+def test_l1_groups_last_end_short_of_or_beyond_the_range(last):
+    """A table whose last end stops short of n, or lies beyond it: every call resolves it the
+    same way (the last segment covers the rest of the range), so the scale an element is
+    quantised with is the mean over the segment it was summed in."""
+    n, W, L = 64 * 700 + 37, 3, 15
+    ends64 = [10, 200, last]
+    case = Case(n, W, seed=26600, m_spread=1.0)
+    heavy_tailed(case, 17, 2.0)
+    for s, (lo, hi) in enumerate(segments_of(ends64, n)):
+        f = 8.0 ** (s - 1)
+        case.g[:, lo:hi] *= f
+        case.m[:, lo:hi] *= f
+    case.snapshot()
+    assert segments_of(ends64, n)[-1] == (200 * 64, n)
+    lr = [HP["lr"], 3 * HP["lr"], 7 * HP["lr"]]
+    out = run_l1_groups(case, L, 1, ends64, lr=lr)
+    check_l1_groups(case, out, L, 1, ends64, lr=lr)
+    # the divergence metric per group follows the same rule
+    end_t = torch.tensor(ends64, dtype=torch.int32, device="cuda")
+    dv = torch.zeros(3, dtype=torch.float64, device="cuda")
+    lc.lc_momentum_divergence_groups(case.m, case.m.stride(0), W, n, end_t, 3, dv)
+    torch.cuda.synchronize()
+    m_now = case.m.cpu().numpy()
+    want = [orc.momentum_divergence(m_now[:, lo:hi]) for lo, hi in segments_of(ends64, n)]
+    assert dv.cpu().numpy().tolist() == want
 
 
 def test_l1_groups_argument_checks():
