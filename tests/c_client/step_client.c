@@ -76,8 +76,17 @@ int main(int argc, char **argv)
 
     hipStream_t stream;
     CHECK_HIP(hipStreamCreate(&stream));
+    /* An error that an unrelated call of the host program leaves pending (here: a copy with
+     * a direction that does not exist, refused on the host before anything reaches the GPU)
+     * must not show up as the status of the library's calls, which report their own
+     * launches only. */
+    const hipError_t planted = hipMemcpy(theta, h_theta, sizeof(float), (hipMemcpyKind)77);
+    if (planted == hipSuccess) { fprintf(stderr, "the copy with an invalid direction was accepted\n"); return 1; }
     CHECK_LC(lc_local_update_pack(g, stride, LC_F32, m, stride, W, n, 0.9f, 1, 0.99f, 1, q, nw * 8, step, LC_ZERO_ALT, stream));
     CHECK_LC(lc_vote_apply_1bit(q, nw, W, n, step, LC_TIE_ZERO, theta, 1e-4f, 0.1f, NULL, 0, NULL, 0, LC_F32, 0, 0.99f, stream));
+    const hipError_t pending = hipGetLastError();      /* read (and cleared) by the host program, not by the library */
+    printf("planted error %d, pending after the library calls: %d\n", (int)planted, (int)pending);
+    if (pending != hipSuccess && pending != planted) { fprintf(stderr, "unexpected pending error %d\n", (int)pending); return 1; }
     CHECK_HIP(hipStreamSynchronize(stream));
 
     FILE *out = fopen(argv[2], "wb");

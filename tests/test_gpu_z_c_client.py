@@ -46,6 +46,7 @@ def test_plain_c_process_matches_the_oracle(n, W, step, tmp_path):
         g.tofile(f)
     run = subprocess.run([exe, state, result], capture_output=True, text=True, timeout=120)
     assert run.returncode == 0, run.stderr
+    assert "planted error" in run.stdout          # the foreign pending error did not become the library's status
     nw = (n + 63) // 64
     with open(result, "rb") as f:
         theta1 = np.fromfile(f, np.float32, n)
