@@ -47,9 +47,9 @@ def parse():
                          "configurations when the headline is c3, none otherwise; \"none\"")
     ap.add_argument("--other-steps", type=int, default=10, help="timed steps of each further configuration")
     ap.add_argument("--copies", type=int, default=2, help="state copies the timed steps alternate between (>= 1)")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 26,
+    ap.add_argument("--cpu-sample", type=int, default=1 << 27,
                     help="parameters in the oracle's all-threads sample (0: skip the CPU leg)")
-    ap.add_argument("--cpu-sample-single", type=int, default=1 << 23,
+    ap.add_argument("--cpu-sample-single", type=int, default=1 << 24,
                     help="parameters in the oracle's single-thread sample")
     ap.add_argument("--cpu-threads", type=int, default=0,
                     help="0 = the cores this process may use, capped at 16 (one GPU's share of the box)")
