@@ -420,15 +420,19 @@ def cpu_baseline(wl, st, torch, sample, sample_single, threads):
 
 
 def read_traffic(workload, kernel):
-    """HBM bytes per launch measured offline with rocprofv3 counters, if a summary for
-    this workload and kernel has been committed under profiles/."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
-    if not os.path.exists(path):
-        return None
-    for line in open(path):
-        parts = line.split("=")
-        if len(parts) == 2 and parts[0].strip() == "traffic_bytes_per_launch." + kernel:
-            return float(parts[1])
+    """HBM bytes per launch measured offline with rocprofv3 counters, if a summary that
+    covers this workload and kernel has been committed under profiles/ (the workload's own
+    file first, then its variants such as ..._p7_sum or ..._vote_then_apply)."""
+    import glob
+    own = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    paths = [own] + sorted(p for p in glob.glob(os.path.join(ROOT, "profiles", "hbm_traffic_%s_*.txt" % workload)))
+    for path in paths:
+        if not os.path.exists(path):
+            continue
+        for line in open(path):
+            parts = line.split("=")
+            if len(parts) == 2 and parts[0].strip() == "traffic_bytes_per_launch." + kernel:
+                return float(parts[1])
     return None
 
 

@@ -37,7 +37,25 @@ def test_traffic_summaries_cover_the_dominant_kernels():
     """bench.py fills roofline.traffic from the committed counter summaries."""
     for name, kernel in (("c1_gpt2s_w8_1bit", "local_update_pack"), ("c2_gpt2s_w8_p4", "local_update_pack"),
                          ("c3_gpt2m_w16_bf16_1bit_mavg", "local_update_pack"),
-                         ("c4_1p3b_w64_prepacked", "vote_apply_1bit"), ("l1_gpt2s_w8_l15", "l1_quantize_pack")):
+                         ("c3_gpt2m_w16_bf16_1bit_mavg", "momentum_avg"),
+                         ("c4_1p3b_w64_prepacked", "vote_apply_1bit"), ("c4_1p3b_w64_prepacked", "pbit_sum_apply"),
+                         ("c4_1p3b_w64_prepacked", "vote_1bit"), ("l1_gpt2s_w8_l15", "l1_quantize_pack")):
         t = bench.read_traffic(name, kernel)
         assert t is not None and t > 1e9, (name, kernel)
     assert bench.read_traffic("no_such_workload", "x") is None
+
+
+def test_default_headline_is_the_largest_full_path_workload():
+    """No flags: c3 is the headline and the other benchmark configurations ride along."""
+    old = sys.argv
+    try:
+        sys.argv = ["bench.py"]
+        args = bench.parse()
+    finally:
+        sys.argv = old
+    assert args.workload == "c3" and args.others == "default" and args.copies == 2 and args.steps == 20
+    for key in ("c0", "c0rot", "c1", "c2", "c4", "c4sum"):
+        wname, kw, copies, _ = bench.OTHERS[key]
+        assert synth.workload(wname).name.startswith(key[:2])
+    assert bench.OTHERS["c4sum"][1] == {"variant": "sum"} and bench.OTHERS["c0rot"][2] == 8
+    assert bench.stats([3.0, 1.0, 2.0, 10.0]) == {"mean": 4.0, "median": 2.5, "min": 1.0}
