@@ -127,3 +127,67 @@ def test_reduction_only_workload_every_element(part, parts):
     done, ties = over_chunks(check, chunk_list)
     assert done == chunk_list[-1][1] - chunk_list[0][0]
     assert ties > 0
+
+
+def test_ternary_workload_every_element():
+    """GPT-2-small shapes, 8 workers, the two-plane ternary wire format of Appendix B.1."""
+    wl = synth.workload("t2")
+    kernels, st, step_no = bench.build_step(wl, torch, lc, synth)
+    n, W = wl.n, wl.W
+    theta0, m0 = st["theta"].clone(), clone_rows(st["m"])
+    for k in kernels:
+        k.fn()
+    torch.cuda.synchronize()
+    hp = dict(beta1=wl.beta1, beta2=wl.beta2, lr=wl.lr, wd=wl.wd)
+
+    def check(lo, hi):
+        where = "t2 [%d, %d)" % (lo, hi)
+        ref = orc.step_ternary(theta0[lo:hi].cpu().numpy(), m0[:, lo:hi].cpu().numpy(), st["g"][:, lo:hi].cpu().numpy(), **hp)
+        w0, w1 = lo // 64, (hi + 63) // 64
+        assert np.array_equal(st["pos"][:, w0:w1].cpu().numpy().view(np.uint64), ref["pos_w"]), "pos planes, " + where
+        assert np.array_equal(st["nz"][:, w0:w1].cpu().numpy().view(np.uint64), ref["nz_w"]), "nz planes, " + where
+        assert worst_excess(st["theta"][lo:hi].cpu().numpy(), ref["theta"]) <= 0.0, "theta, " + where
+        assert worst_excess(st["m"][:, lo:hi].cpu().numpy(), ref["m"]) <= 0.0, "momentum, " + where
+        return hi - lo, int((ref["u"] == 0).sum())
+
+    done, zeros = over_chunks(check, spans(n))
+    assert done == n and zeros > 0
+
+
+def test_l1_workload_every_element():
+    """GPT-2-small shapes, 8 workers, L = 15 (the 8-bit L1-quantised allreduce of Appendix
+    F.1): the exact means over all elements, then every level byte, level sum, parameter and
+    momentum."""
+    wl = synth.workload("l1")
+    kernels, st, step_no = bench.build_step(wl, torch, lc, synth)
+    n, W, L = wl.n, wl.W, wl.levels
+    theta0, m0 = st["theta"].clone(), clone_rows(st["m"])
+    for k in kernels:
+        k.fn()
+    torch.cuda.synchronize()
+    means = st["mean_abs"].cpu().numpy()
+
+    def mean_of(w):
+        c = orc.local_c(m0[w].cpu().numpy(), st["g"][w].cpu().numpy(), wl.beta1)
+        return orc.mean_abs(c)
+
+    with ThreadPoolExecutor(max_workers=min(W, THREADS)) as ex:
+        want = list(ex.map(mean_of, range(W)))
+    assert means.tolist() == want, "mean |c| over all elements"
+
+    def check(lo, hi):
+        where = "l1 [%d, %d)" % (lo, hi)
+        mm, gg = m0[:, lo:hi].cpu().numpy(), st["g"][:, lo:hi].cpu().numpy()
+        lev = np.stack([orc.l1_levels(orc.local_c(mm[w], gg[w], wl.beta1), means[w], L) for w in range(W)])
+        fields = (lev.astype(np.int16) + L).astype(np.uint8)
+        assert np.array_equal(st["q"][:, lo:hi].cpu().numpy(), fields), "level bytes, " + where
+        K, S, u = orc.level_sum_sign(fields, L, step_no[0], orc.TIE_ZERO)
+        assert np.array_equal(st["sum_out"][lo:hi].cpu().numpy().astype(np.int32), K), "level sums, " + where
+        ref_theta = orc.apply(theta0[lo:hi].cpu().numpy(), u, wl.lr, wl.wd)
+        assert worst_excess(st["theta"][lo:hi].cpu().numpy(), ref_theta) <= 0.0, "theta, " + where
+        m_ref = np.stack([orc.momentum(mm[w], gg[w], wl.beta2) for w in range(W)])
+        assert worst_excess(st["m"][:, lo:hi].cpu().numpy(), m_ref) <= 0.0, "momentum, " + where
+        return hi - lo, int((u == 0).sum())
+
+    done, ties = over_chunks(check, spans(n))
+    assert done == n and ties > 0
