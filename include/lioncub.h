@@ -28,7 +28,10 @@
  *    (i mod 8/C) of byte floor(i*C/8), low bits first; ceil(n*C/8) bytes per row; pad
  *    fields are written as 0.  Bytes past that count are neither read nor written.
  *  - Alignment: theta, m, g, field buffers and sum_out: base and every row 16-byte
- *    aligned.  1-bit buffers and vote planes: 8-byte aligned.
+ *    aligned.  1-bit buffers and vote planes: 8-byte aligned.  (Speed, not correctness:
+ *    rows that start a large power of two apart -- a row stride of exactly 64 MiB, say --
+ *    fall on the same memory channels; measured with 64 rows that costs a fifth of the
+ *    bandwidth.  Pad the stride by a few hundred bytes in that case.)
  *  - `step` is the caller's 1-based iteration counter; only its parity is used, by the
  *    alternating rule of Appendix B.1 (zero -> +1 on odd iterations, -1 on even ones).
  *  - Buffers named in one call must not overlap each other.

@@ -11,8 +11,8 @@
 // better; their results are the same bits.
 //
 // General kernel.
-// Every wave works alone on kAggWave = 1024 consecutive elements (16 packed words, four
-// 256-element tiles) and is short-lived: on MI355X many small independent waves stream
+// Every wave works alone on 1024 consecutive elements (16 packed words, four 256-element
+// tiles; 512 elements for 32 and more 1-bit rows) and is short-lived: on MI355X many small independent waves stream
 // faster than few long ones.  Three phases:
 //
 //  A  count   1-bit rows: lane = 16 * phase + j.  Lane (phase, j) loads word j of rows
@@ -48,7 +48,7 @@ namespace lc {
 // of which keeps many loads in flight (measured on the W = 64 vote: 32 waves per unit
 // 5.35 TB/s, 12 waves 5.47, 8 waves 5.6, 4 waves 5.0).
 #ifndef LC_AGG_LDS
-#define LC_AGG_LDS 32768  // general kernel on 32 and more 1-bit rows: five workgroups = 10 waves per compute unit (+1.5 %)
+#define LC_AGG_LDS 32768  // general kernel on 32 and more 1-bit rows with 16 words per wave: 10 waves per compute unit (+1.5 %)
 #endif
 #ifndef LC_AGG_BATCH16
 #define LC_AGG_BATCH16 1  // 1-bit rows of the general kernel: sixteen loads in flight per lane instead of eight (+1.5 % at W = 64)
@@ -70,11 +70,12 @@ constexpr int kWaves = kAggThreads / kWave;
 #ifndef LC_AGG_WORDS
 #define LC_AGG_WORDS 16
 #endif
-constexpr int kAggWords = LC_AGG_WORDS;       // packed words per wave
-constexpr int kAggWave = kAggWords * 64;      // elements per wave
-constexpr int kAggBlock = kAggWave * kWaves;  // elements per workgroup
-constexpr int kAggTiles = kAggWave / 256;
-constexpr int kPhases = kWave / kAggWords;    // lanes that share a word in phase A
+constexpr int kAggWordsDefault = LC_AGG_WORDS;  // packed words per wave
+#ifndef LC_AGG_WORDS_MANY
+#define LC_AGG_WORDS_MANY 8
+#endif
+constexpr int kAggWordsMany = LC_AGG_WORDS_MANY;  // ... for 32 and more 1-bit rows
+constexpr int kAggManyRows = 32;
 
 enum { IN_PLANES = 0, IN_BITS = 1 /* 2, 4, 8: field width */, IN_TERNARY = 16 /* pos + nz rows */ };
 
@@ -237,9 +238,15 @@ __device__ __forceinline__ void store_words(char *p, const uint32_t (&x)[NWD])
     }
 }
 
-template <int IN, int GDT, bool APPLY, bool MOM, bool KOUT>
+template <int IN, int GDT, bool APPLY, bool MOM, bool KOUT, int WORDS>
 __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams P)
 {
+    // WORDS packed words per wave: 16 (1024 elements, four tiles) in general, 8 for 32 and more
+    // 1-bit rows, where shorter waves with the same loads in flight per lane stream faster
+    constexpr int kAggWords = WORDS;
+    constexpr int kAggWave = kAggWords * 64;    // elements per wave
+    constexpr int kAggTiles = kAggWave / 256;
+    constexpr int kPhases = kWave / kAggWords;  // lanes that share a word in phase A
     __shared__ uint64_t s_pos[kWaves][kAggWords];
     __shared__ uint64_t s_nz[kWaves][kAggWords];
     __shared__ uint64_t s_cnt[KOUT ? kWaves : 1][KOUT ? 8 : 1][KOUT ? kAggWords : 1];
@@ -994,9 +1001,18 @@ static hipError_t launch_tile(const AggParams &P, hipStream_t s)
 template <int IN, int GDT, bool APPLY, bool MOM, bool KOUT>
 static hipError_t launch_one(const AggParams &P, hipStream_t s)
 {
-    const unsigned grid = static_cast<unsigned>((P.n + kAggBlock - 1) / kAggBlock);
-    const unsigned lds = (IN == IN_BITS && P.W >= 32) ? LC_AGG_LDS : 0;
-    return launch(aggregate_kernel<IN, GDT, APPLY, MOM, KOUT>, grid, kAggThreads, lds, s, P);
+    if constexpr (IN == IN_BITS) {
+        if (P.W >= kAggManyRows) {
+            // many rows: shorter waves; with 16 words per wave fewer waves per compute unit (dynamic LDS as a cap)
+            constexpr size_t block = static_cast<size_t>(kAggWordsMany) * 64 * kWaves;
+            const unsigned lds = kAggWordsMany >= 16 ? LC_AGG_LDS : 0;
+            return launch(aggregate_kernel<IN, GDT, APPLY, MOM, KOUT, kAggWordsMany>, static_cast<unsigned>((P.n + block - 1) / block),
+                          kAggThreads, lds, s, P);
+        }
+    }
+    constexpr size_t block = static_cast<size_t>(kAggWordsDefault) * 64 * kWaves;  // elements per workgroup
+    return launch(aggregate_kernel<IN, GDT, APPLY, MOM, KOUT, kAggWordsDefault>, static_cast<unsigned>((P.n + block - 1) / block),
+                  kAggThreads, 0, s, P);
 }
 
 template <int IN, bool KOUT>
