@@ -608,114 +608,73 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(const AggParams 
 // Vote only (planes out, nothing applied): the local reduction of the 1-bit compressed
 // allreduce between its all-to-all and its allgather (Section 3).  There is no element-wise
 // phase, so the word-per-lane layout is kept throughout: a lane owns one 64-bit word of every
-// row (512 contiguous bytes per row and wave instruction) in each of kVoteCols consecutive
-// 64-word columns that its wave walks through.  Rows are fetched eight at a time into two
-// register sets that take turns: the next eight rows -- of this column, or the first eight of
-// the wave's next column -- are requested before the current eight are counted, so that a
-// wave always has loads in flight, also while it stores a column's planes.
+// row (512 contiguous bytes per row and wave instruction).  Rows are fetched eight at a time;
+// for W a multiple of 16 two register sets take turns, the next eight rows requested before
+// the current eight are counted, so that a wave always has loads in flight.  (Letting a wave
+// walk on through 2 .. 8 further columns, with the first rows of the next column requested
+// before a column's planes are stored, was slower: 5.1 .. 4.9 against 5.4 TB/s.)
 #ifndef LC_VOTE_THREADS
 #define LC_VOTE_THREADS 256
-#endif
-#ifndef LC_VOTE_COLS
-#define LC_VOTE_COLS 1
 #endif
 #ifndef LC_VOTE_PIPE
 #define LC_VOTE_PIPE 1
 #endif
 constexpr int kVoteThreads = LC_VOTE_THREADS;
-constexpr int kVoteCols = LC_VOTE_COLS;
 
-// eight consecutive rows of the lane's word, no guards: straight-line loads
+// eight consecutive rows of the lane's word, no guards: straight-line loads (a guard on each
+// load makes the compiler wait after every one of them)
 __device__ __forceinline__ void vote_load8(uint64_t (&x)[8], const uint64_t *src, size_t stride)
 {
 #pragma unroll
     for (int i = 0; i < 8; ++i) x[i] = ld_packed(src + static_cast<size_t>(i) * stride);
 }
 
-__device__ __forceinline__ void vote_store(const AggParams &P, uint64_t (&c)[8], size_t jw, size_t nw)
-{
-    uint64_t gt, eq, pos, nz;
-    compare_planes(c, P.thresh, gt, eq);
-    vote_planes(gt, eq, P.tie_possible != 0, P.tie, pos, nz);
-    if (jw < nw) {
-        const uint64_t vm = valid_mask(jw * 64, P.n);
-        if (P.vote_pos) P.vote_pos[jw] = pos & vm;
-        if (P.vote_nz) P.vote_nz[jw] = nz & vm;
-    }
-#pragma unroll
-    for (int k = 0; k < 8; ++k) c[k] = 0ull;
-}
-
-// PIPE (W a multiple of 16): the rows of the wave's columns form one sequence of groups of
-// sixteen; two register sets take turns, and every load of the steady state is issued a
-// whole csa8 before its value is needed.  Otherwise: eight rows at a time, rows at or beyond
-// W (uniform) skipped.
+// PIPE: W is a multiple of 16.  Otherwise eight rows at a time through one register set, rows
+// at or beyond W (uniform) skipped.
 template <bool PIPE>
 __global__ __launch_bounds__(kVoteThreads) void vote_only_kernel(const AggParams P)
 {
-    const size_t nw = (P.n + 63) / 64;
-    const int lane = threadIdx.x & (kWave - 1);
-    // first word of the wave's first column
-    const size_t wave_first = ((static_cast<size_t>(blockIdx.x) * (kVoteThreads / kWave) + wave_index()) * kVoteCols) * kWave;
-    if (wave_first >= nw) return;
+    const size_t jw = static_cast<size_t>(blockIdx.x) * kVoteThreads + threadIdx.x;
+    const size_t n = P.n;
+    if (jw * 64 >= n) return;
     const int W = P.W;
     const size_t stride = P.q_stride_bytes / 8;
-    const uint64_t *q = static_cast<const uint64_t *>(P.q);
+    const uint64_t *cur = static_cast<const uint64_t *>(P.q) + jw;
     uint64_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    // columns of this wave that hold words (uniform); a lane beyond the last word reads word 0
-    const size_t left = (nw - wave_first + kWave - 1) / kWave;
-    const int cols = left < static_cast<size_t>(kVoteCols) ? static_cast<int>(left) : kVoteCols;
-    auto word = [&](int t) { return wave_first + static_cast<size_t>(t) * kWave + lane; };
-    auto column = [&](int t) { const size_t j = word(t); return q + (j < nw ? j : 0); };
     if constexpr (PIPE) {
-        uint64_t xa[8], xb[8];
         const size_t half = 8 * stride;
-        int t = 0, w = 0;                       // column and first row of the current group of sixteen
-        const uint64_t *cur = column(0);        // its first row, this lane's word
+        uint64_t xa[8], xb[8];
         vote_load8(xa, cur, stride);
-        for (;;) {
-            // the group after this one: further down this column, or the top of the next
-            const bool col_end = w + 16 >= W;
-            const bool last = col_end && t + 1 >= cols;
-            if (last) break;
-            const uint64_t *next = col_end ? column(t + 1) : cur + 2 * half;
+        for (int w = 16; w < W; w += 16) {  // every group of sixteen rows but the last
             vote_load8(xb, cur + half, stride);
             csa8(c, xa);
-            vote_load8(xa, next, stride);
+            cur += 2 * half;
+            vote_load8(xa, cur, stride);
             csa8(c, xb);
-            if (col_end) {
-                vote_store(P, c, word(t), nw);
-                ++t;
-                w = 0;
-            } else {
-                w += 16;
-            }
-            cur = next;
         }
         vote_load8(xb, cur + half, stride);
         csa8(c, xa);
         csa8(c, xb);
-        vote_store(P, c, word(t), nw);
     } else {
-#pragma unroll 1
-        for (int t = 0; t < cols; ++t) {
-            const uint64_t *qp = column(t);
-            for (int w = 0; w < W; w += 8) {
-                uint64_t x[8];
+        for (int w = 0; w < W; w += 8) {
+            uint64_t x[8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) x[i] = (w + i < W) ? ld_packed(qp + static_cast<size_t>(w + i) * stride) : 0ull;
-                csa8(c, x);
-            }
-            vote_store(P, c, word(t), nw);
+            for (int i = 0; i < 8; ++i) x[i] = (w + i < W) ? ld_packed(cur + static_cast<size_t>(w + i) * stride) : 0ull;
+            csa8(c, x);
         }
     }
+    const uint64_t vm = valid_mask(jw * 64, n);
+    uint64_t gt, eq, pos, nz;
+    compare_planes(c, P.thresh, gt, eq);
+    vote_planes(gt, eq, P.tie_possible != 0, P.tie, pos, nz);
+    if (P.vote_pos) P.vote_pos[jw] = pos & vm;
+    if (P.vote_nz) P.vote_nz[jw] = nz & vm;
 }
 
 static hipError_t launch_vote_only(const AggParams &P, hipStream_t s)
 {
     const size_t nw = (P.n + 63) / 64;
-    constexpr size_t per = static_cast<size_t>(kVoteThreads) * kVoteCols;  // words per workgroup
-    const unsigned grid = static_cast<unsigned>((nw + per - 1) / per);
+    const unsigned grid = static_cast<unsigned>((nw + kVoteThreads - 1) / kVoteThreads);
     if (LC_VOTE_PIPE && P.W % 16 == 0) return launch(vote_only_kernel<true>, grid, kVoteThreads, LC_VOTE_LDS, s, P);
     return launch(vote_only_kernel<false>, grid, kVoteThreads, LC_VOTE_LDS, s, P);
 }
