@@ -65,6 +65,9 @@ def parse():
     ap.add_argument("--groups", action="store_true",
                     help="workloads with a tensor list (c1, c2, c3, l1, t2): per-tensor learning rates (and, for L1, per-tensor "
                          "scales) through the group-table entry points, still one launch set for the arena")
+    ap.add_argument("--divergence", action="store_true",
+                    help="c1, c2, c3: also take the divergence of the workers' momenta in every step (one value, or "
+                         "one per tensor with --groups), after the momentum update and before any averaging")
     ap.add_argument("--split", action="store_true",
                     help="pre-packed workload (c4): lc_vote_1bit then lc_apply_update, the two calls either side of "
                          "the allgather of the vote, instead of the fused lc_vote_apply_1bit")
@@ -125,7 +128,7 @@ def group_table(wl, torch, dev):
 
 
 def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False, variant="vote", one_plane=False,
-               share=None):
+               share=None, divergence=False):
     """Allocate the workload on cuda:0 and return (kernels, state, step counter) for one
     step.  state["rmw"] names the buffers a step writes in place.  share: a state dict of
     an earlier copy whose read-only packed rows are reused (pre-packed workload)."""
@@ -343,6 +346,21 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
                 lambda: lc.lc_pbit_sum_apply(q, q.stride(0), C, W, n, wl.p, sum_out, step_no[0], lc.LC_TIE_ZERO, theta,
                                              hp["lr"], hp["wd"], None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
                 n * (W * C / 8 + C / 8 + 8)))
+    if divergence:
+        # Section 5.1's metric, taken where a training loop would take it: after the momentum update, before
+        # any averaging.  One double per call, or one per tensor with the group table.
+        if groups and wl.tensors:
+            if "end64" not in st:
+                st["end64"] = group_table(wl, torch, dev)[0]
+            d_end, d_out = st["end64"], torch.zeros(len(wl.tensors), dtype=torch.float64, device=dev)
+            kernels.append(Kernel("momentum_divergence_groups",
+                                  lambda: lc.lc_momentum_divergence_groups(m, m.stride(0), W, n, d_end, len(wl.tensors), d_out),
+                                  n * W * 4))
+        else:
+            d_out = torch.zeros(1, dtype=torch.float64, device=dev)
+            kernels.append(Kernel("momentum_divergence", lambda: lc.lc_momentum_divergence(m, m.stride(0), W, n, d_out),
+                                  n * W * 4))
+        st["max_std"] = d_out
     if wl.momentum_avg:
         kernels.append(Kernel("momentum_avg", lambda: lc.lc_momentum_avg(m, m.stride(0), W, n), n * W * 8))
     return kernels, st, step_no
@@ -550,8 +568,10 @@ def main():
     lc.load()
     torch.cuda.set_device(0)
     wl = synth.workload(args.workload)
+    if args.divergence and wl.mode == "prepacked":
+        sys.exit("bench.py: --divergence needs a workload with one momentum row per worker (c0 .. c3, l1, t2)")
     build_kw = dict(per_tensor=args.per_tensor, groups=args.groups, split=args.split,
-                    variant="sum" if args.sum else "vote", one_plane=args.one_plane)
+                    variant="sum" if args.sum else "vote", one_plane=args.one_plane, divergence=args.divergence)
     run = Run(wl, torch, lc, synth, 1 if args.graph else args.copies, **build_kw)
     names = run.names                                   # what was built, not what was asked for
     torch.cuda.synchronize()
@@ -626,7 +646,7 @@ def main():
     # the other benchmark configurations, one after the other, each freed before the next
     if args.others == "default":
         others = ["c0", "c0rot", "c1", "c2", "c4", "c4sum"] if wl.name.startswith("c3") and not (
-            args.per_tensor or args.groups or args.graph) else []
+            args.per_tensor or args.groups or args.graph or args.divergence) else []
     elif args.others in ("none", ""):
         others = []
     else:

@@ -156,6 +156,35 @@ __device__ __forceinline__ int group_walk(const uint32_t *end64, int G, int s, u
     while (s < G - 1 && b >= end64[s]) ++s;
     return s;
 }
+// group_find for a whole wave without a chain of dependent loads: for ascending ends the
+// segment of block b is the number of ends (the last one aside, which counts as infinite) at
+// or before b.  The 64 lanes hold up to kGroupEndsPerLane ends each -- lane l the ends
+// l, l + 64, ... -- requested in one go (GroupEnds::load, which a kernel places ahead of its
+// bulk loads so that the table arrives first); GroupEnds::count then needs only lane masks.
+// Every lane must be active in both.  A table that does not ascend still gives an index in
+// [0, G - 1].
+constexpr int kGroupEndsPerLane = 16;
+constexpr int kGroupCountMax = 64 * kGroupEndsPerLane;
+struct GroupEnds {
+    uint32_t v[kGroupEndsPerLane];
+    __device__ __forceinline__ void load(const uint32_t *end64, int G, int lane)
+    {
+#pragma unroll
+        for (int k = 0; k < kGroupEndsPerLane; ++k) {
+            const int idx = lane + 64 * k;
+            v[k] = 0xFFFFFFFFu;  // beyond every block
+            if (64 * k < G - 1 && idx < G - 1) v[k] = end64[idx];
+        }
+    }
+    __device__ __forceinline__ int count(int G, uint32_t b) const
+    {
+        int s = 0;
+#pragma unroll
+        for (int k = 0; k < kGroupEndsPerLane; ++k)
+            if (64 * k < G - 1) s += __builtin_popcountll(__ballot(v[k] <= b));
+        return s;
+    }
+};
 // the blocks [lo, hi) of segment s under the same rule (n64 = blocks in the range)
 __device__ __forceinline__ uint32_t group_lo64(const uint32_t *end64, int s, uint32_t n64)
 {

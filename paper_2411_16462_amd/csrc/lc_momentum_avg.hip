@@ -81,7 +81,8 @@ hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStre
 // ---- divergence of the workers' momenta (Section 5.1, the quantity of Figure 6) --------
 // max over elements of the standard deviation across the W workers (divisor W), in fp64
 // with the workers taken in order, so that the result equals a sequential evaluation bit
-// for bit; the maximum is order-free.  Reads W * 4 bytes per element, writes one double.
+// for bit; the maximum is order-free.  Reads W * 4 bytes per element, writes one double
+// (or one per segment of a group table).
 __global__ void divergence_zero_kernel(double *out, int count)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -114,20 +115,67 @@ __device__ __forceinline__ void publish_std(double *dst, double ss, int W)
     if (bits > *reinterpret_cast<volatile unsigned long long *>(p)) atomicMax(p, bits);
 }
 
-// GROUPED: out[s] receives the maximum over segment s of a group table (segment ends in
-// units of 64 elements).  A wave whose 256 elements lie in one segment reduces first; a wave
-// that straddles a boundary lets every lane publish its own value.
-template <bool GROUPED>
-__global__ __launch_bounds__(256) void momentum_divergence_kernel(const float *__restrict__ m, size_t stride, int W, size_t n,
-                                                                  double *__restrict__ out,
-                                                                  const uint32_t *__restrict__ end64, int G)
+#ifndef LC_DIV_STREAMS
+#define LC_DIV_STREAMS 1024  // measured alike from 256 to 2048; 8 and 64 are slower
+#endif
+constexpr unsigned kDivStreams = LC_DIV_STREAMS;
+#ifndef LC_DIV_LDS
+#define LC_DIV_LDS 0  // unused dynamic LDS per workgroup: a tuning knob that caps occupancy
+#endif
+
+// Largest sum of squared deviations among the lane's four elements e .. e + 3.  CAP > 0:
+// the wave's 256 elements all lie below n and W <= CAP; every row is requested once, up
+// front, and both passes (sum, then squared deviations, workers in order) run from
+// registers -- 6.8 TB/s at 16 rows against 3.3 TB/s for the form that reads the rows a
+// second time.  A row index at or beyond W re-reads the last row (a cache hit) and is left
+// out of the arithmetic.  CAP = 0: any W, ragged end; the second pass reads the rows again.
+template <int CAP, class Between>
+__device__ __forceinline__ double divergence_worst(const float *__restrict__ m, size_t stride, int W, size_t n, size_t tile,
+                                                   unsigned lane_off, Between &&between)
 {
-    __shared__ double s_max[4];
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = wave_index();
-    const size_t e = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
-    double worst = 0.0;  // largest sum of squared deviations of this lane's elements
-    if (e < n) {
+    const size_t e = tile + lane_off;
+    double worst = 0.0;
+    const double dw = static_cast<double>(W);
+    if constexpr (CAP > 0) {
+        f32x4 x[CAP];
+#pragma unroll
+        for (int w = 0; w < CAP; ++w) {
+            // uniform row address plus a 32-bit lane offset: no address registers per row
+            const float *row = m + static_cast<size_t>(w < W ? w : W - 1) * stride + tile;
+            x[w] = load4(row + lane_off);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // every row is requested before the first is used
+        between();                          // work that does not depend on the rows runs while they are in flight
+        double sum[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int w = 0; w < CAP; ++w) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (w < W) sum[k] += static_cast<double>(x[w][k]);
+        }
+        double mean[4], ss[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) mean[k] = sum[k] / dw;
+        // the second pass converts the rows again: keeping the first pass's doubles would
+        // triple the registers per lane
+#pragma unroll
+        for (int w = 0; w < CAP; ++w) asm volatile("" : "+v"(x[w]));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int w = 0; w < CAP; ++w) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (w < W) {
+                    const double d = static_cast<double>(x[w][k]) - mean[k];
+                    ss[k] += d * d;
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (ss[k] > worst) worst = ss[k];
+    } else {
+        between();
         double sum[4] = {0.0, 0.0, 0.0, 0.0};
         for (int w = 0; w < W; ++w) {
             const f32x4 v = load4_guarded(m + static_cast<size_t>(w) * stride, e, n);
@@ -136,7 +184,7 @@ __global__ __launch_bounds__(256) void momentum_divergence_kernel(const float *_
         }
         double mean[4], ss[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-        for (int k = 0; k < 4; ++k) mean[k] = sum[k] / static_cast<double>(W);
+        for (int k = 0; k < 4; ++k) mean[k] = sum[k] / dw;
         for (int w = 0; w < W; ++w) {  // second pass: the rows are still in cache
             const f32x4 v = load4_guarded(m + static_cast<size_t>(w) * stride, e, n);
 #pragma unroll
@@ -149,23 +197,87 @@ __global__ __launch_bounds__(256) void momentum_divergence_kernel(const float *_
         for (int k = 0; k < 4; ++k)
             if (e + k < n && ss[k] > worst) worst = ss[k];
     }
+    return worst;
+}
+
+// GROUPED: out[s] receives the maximum over segment s of a group table (segment ends in
+// units of 64 elements).  A wave whose 256 elements lie in one segment reduces first; a wave
+// that straddles a boundary lets every lane publish its own value.
+template <int CAP, bool GROUPED>
+__global__ __launch_bounds__(256) void momentum_divergence_kernel(const float *__restrict__ m, size_t stride, int W, size_t n,
+                                                                  double *__restrict__ out,
+                                                                  const uint32_t *__restrict__ end64, int G)
+{
+    __shared__ double s_max[4];
+    __shared__ int s_seg[4];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = wave_index();
+    // GROUPED: workgroup b works in stream b % S at position b / S, so that the workgroups in
+    // flight at one time lie in S distant places.  In launch order the workgroups of a segment
+    // would all run at once, every one of them would read the segment's slot before any has
+    // written it, and every one would then send its atomic to that one address (measured on
+    // 148 equal segments of 124 M elements: 1.27 ms against 0.58 ms).
+    size_t wg = blockIdx.x;
+    if (GROUPED) wg = static_cast<size_t>(blockIdx.x % kDivStreams) * (gridDim.x / kDivStreams) + blockIdx.x / kDivStreams;
+    const size_t tile = (wg * 4 + wave) * 256;  // the wave's first element (uniform)
+    const size_t e = tile + static_cast<size_t>(lane) * 4;
+    // GROUPED: the segment of the wave's first 64-element block (uniform), then each lane
+    // walks on to the segment of its own block; lanes past n stay with the last.  Small
+    // tables are requested here, ahead of the rows, and resolved with lane masks once the
+    // rows are requested; large ones are bisected, a chain of dependent loads that runs
+    // between the request for the rows and their use.
+    int seg = G - 1;
+    GroupEnds ends;
+    const bool counted = GROUPED && G <= kGroupCountMax;
+    if (counted) ends.load(end64, G, lane);
+    auto find_group = [&] {
+        if (GROUPED) {
+            const uint32_t b = static_cast<uint32_t>(tile / 64);
+            int first;
+            bool one = false;  // the wave's four blocks lie in one segment
+            if (counted) {
+                first = ends.count(G, b);
+                one = ends.count(G, b + 3) == first;
+            } else {
+                first = group_find(end64, G, b);
+            }
+            if (e < n) seg = one ? first : group_walk(end64, G, first, static_cast<uint32_t>(e / 64));
+        }
+    };
+    double worst = 0.0;  // largest sum of squared deviations of this lane's elements
+    if (CAP > 0 && tile + 256 <= n) worst = divergence_worst<CAP>(m, stride, W, n, tile, lane * 4u, find_group);
+    else {
+        find_group();  // with every lane active
+        if (e < n) worst = divergence_worst<0>(m, stride, W, n, tile, lane * 4u, [] {});
+    }
     unsigned long long bits = static_cast<unsigned long long>(__double_as_longlong(worst));
     if (GROUPED) {
-        // segment of the wave's first 64-element block by bisection (uniform), then each
-        // lane walks on to the segment of its own block; lanes past n stay with the last
-        const size_t first = (static_cast<size_t>(blockIdx.x) * 256 + static_cast<size_t>(wave) * kWave) * 4;
-        int seg = group_find(end64, G, static_cast<uint32_t>(first / 64));
-        if (e < n) {
-            seg = group_walk(end64, G, seg, static_cast<uint32_t>(e / 64));
-        } else {
-            seg = G - 1;
-        }
+        // A wave inside one segment reduces and hands its value to the workgroup; a wave
+        // across a boundary publishes lane by lane.  Waves of one segment are neighbours:
+        // one publication per run of equal segments, so that the segment's slot -- one
+        // address for every reader on the chip -- is touched once per workgroup at most.
         const int seg0 = __builtin_amdgcn_readfirstlane(seg);
+        int mine = -1;
         if (__ballot(seg != seg0) == 0) {
             bits = wave_max_bits(bits, lane);
-            if (lane == 0) publish_std(out + seg0, __longlong_as_double(static_cast<long long>(bits)), W);
+            mine = seg0;
         } else {
             publish_std(out + seg, worst, W);
+        }
+        if (lane == 0) {
+            s_max[wave] = __longlong_as_double(static_cast<long long>(bits));
+            s_seg[wave] = mine;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int r = 0; r < 4;) {
+                const int sg = s_seg[r];
+                double b = s_max[r];
+                int q = r + 1;
+                for (; q < 4 && s_seg[q] == sg; ++q) b = s_max[q] > b ? s_max[q] : b;
+                if (sg >= 0) publish_std(out + sg, b, W);
+                r = q;
+            }
         }
         return;
     }
@@ -185,9 +297,19 @@ hipError_t launch_momentum_divergence(const float *m, size_t stride, int W, size
     const int count = n_groups > 0 ? n_groups : 1;
     hipError_t e = launch(divergence_zero_kernel, (count + 255) / 256, 256, 0, s, out, count);
     if (e != hipSuccess || n == 0) return e;
-    const unsigned grid = static_cast<unsigned>((n + 1023) / 1024);
-    if (n_groups > 0) return launch(momentum_divergence_kernel<true>, grid, 256, 0, s, m, stride, W, n, out, end64, n_groups);
-    return launch(momentum_divergence_kernel<false>, grid, 256, 0, s, m, stride, W, n, out, static_cast<const uint32_t *>(nullptr), 0);
+    unsigned grid = static_cast<unsigned>((n + 1023) / 1024);
+    if (n_groups > 0) grid = (grid + kDivStreams - 1) / kDivStreams * kDivStreams;  // whole streams; the surplus workgroups lie beyond n
+    const uint32_t *none = nullptr;
+#define LC_LAUNCH(CAP)                                                                                                       \
+    return n_groups > 0 ? launch(momentum_divergence_kernel<CAP, true>, grid, 256, LC_DIV_LDS, s, m, stride, W, n, out, end64, n_groups) \
+                        : launch(momentum_divergence_kernel<CAP, false>, grid, 256, LC_DIV_LDS, s, m, stride, W, n, out, none, 0)
+    if (W <= 4) LC_LAUNCH(4);
+    if (W <= 8) LC_LAUNCH(8);
+    if (W <= 16) LC_LAUNCH(16);
+    if (W <= 32) LC_LAUNCH(32);
+    if (W <= 64) LC_LAUNCH(64);
+    LC_LAUNCH(0);
+#undef LC_LAUNCH
 }
 
 }  // namespace lc

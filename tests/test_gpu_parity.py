@@ -388,6 +388,40 @@ def test_momentum_divergence_per_group(W):
     assert lc.lc_momentum_divergence_groups(case.m, case.m.stride(0), W, n, end_t, 0, out, check=False) == lc.LC_ERR_SIZE
 
 
+@pytest.mark.parametrize("G,W,longest", [(64, 3, 6), (65, 8, 6), (200, 16, 6), (1024, 4, 6), (1025, 5, 6), (3000, 2, 6),
+                                         (700, 33, 6), (300, 70, 6), (200, 16, 400), (40, 4, 9000)])
+def test_momentum_divergence_many_groups(G, W, longest):
+    """Group tables on either side of what the kernel resolves with lane masks (up to 1024
+    groups) and of what it bisects, with every row count class (rows held in registers up
+    to 64, read twice beyond): random segment lengths of 0 to `longest` blocks -- short ones,
+    so that most waves straddle a boundary, and long ones, so that the launch has several
+    thousand workgroups -- a ragged end, each value against the oracle on its own segment."""
+    rng = np.random.default_rng(G * 7 + W)
+    ends64 = np.cumsum(rng.integers(0, longest + 1, G)).astype(np.int64)
+    n = int(ends64[-1]) * 64 - 37
+    case = Case(n, W, seed=14700 + G + W, m_spread=0.3)
+    bounds = [0] + [min(int(e) * 64, n) for e in ends64]
+    scale = torch.ones(n, device="cuda")
+    for s in range(G):
+        scale[bounds[s]:bounds[s + 1]] = 2.0 ** (s % 7)
+    case.m *= scale
+    case.snapshot()
+    end_t = torch.tensor(ends64, dtype=torch.int64).to(torch.int32).cuda()
+    out = torch.full((G,), -1.0, dtype=torch.float64, device="cuda")
+    lc.lc_momentum_divergence_groups(case.m, case.m.stride(0), W, n, end_t, G, out)
+    whole = torch.full((1,), -1.0, dtype=torch.float64, device="cuda")
+    lc.lc_momentum_divergence(case.m, case.m.stride(0), W, n, whole)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    for s in range(G):
+        lo, hi = bounds[s], bounds[s + 1]
+        ref = orc.momentum_divergence(case.m0[:, lo:hi]) if hi > lo else 0.0
+        assert abs(got[s] - ref) <= 1e-12 * ref, "segment %d of %d [%d, %d): %r vs %r" % (s, G, lo, hi, got[s], ref)
+    assert got.max() == float(whole[0])
+    ref = orc.momentum_divergence(case.m0)
+    assert abs(float(whole[0]) - ref) <= 1e-12 * ref
+
+
 def test_momentum_sync_ranges_policy():
     """Selected ranges only, and only on every k-th iteration (Section 6.2: head and
     embedding every ten iterations)."""

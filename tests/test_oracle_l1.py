@@ -54,7 +54,22 @@ def test_mean_abs_is_the_correctly_rounded_exact_sum(seed):
     want = math.fsum(abs(float(v)) for v in x) / n
     assert orc.mean_abs(x) == want
     assert orc.mean_abs(np.zeros(5, np.float32)) == 0.0
+    assert orc.mean_abs(np.zeros(0, np.float32)) == 0.0
     assert math.isnan(orc.mean_abs(np.array([1.0, np.inf], np.float32)))
+
+
+def test_mean_abs_of_denormals_alone_is_exact():
+    """Denormals carry no hidden bit and share the smallest exponent: a sum made of them
+    alone, and of them beside the smallest normals, is a small integer times 2^-149."""
+    tiny = 2.0 ** -149
+    x = np.array([tiny, -3 * tiny, 5 * tiny, -(2.0 ** -127), 0.0, -0.0, 0.0, 0.0], np.float32)
+    assert np.all(np.abs(x) < np.float32(2.0 ** -126))
+    assert Fraction(orc.mean_abs(x)) == Fraction(1 + 3 + 5 + 2 ** 22, 8) * Fraction(1, 2 ** 149)
+    y = np.array([2.0 ** -126, 7 * tiny, -(2.0 ** -125), -tiny], np.float32)      # two normals, two denormals
+    assert Fraction(orc.mean_abs(y)) == Fraction(2 ** 23 + 7 + 2 ** 24 + 1, 4) * Fraction(1, 2 ** 149)
+    rng = np.random.default_rng(5)
+    z = (rng.integers(-(2 ** 23) + 1, 2 ** 23, 4096) * tiny).astype(np.float32)   # every denormal pattern is fair game
+    assert Fraction(orc.mean_abs(z)) == Fraction(int(np.abs(np.round(z.astype(np.float64) / tiny)).sum()), 4096) / 2 ** 149
 
 
 def test_mean_abs_does_not_depend_on_order_and_beats_naive_fp32():

@@ -101,6 +101,41 @@ def test_bit_budget_from_paper():
         orc.count_sign(np.repeat(b, bad, 0), 1, p=4)
     assert e.value.code == orc.ERR_RANGE
     orc.count_sign(np.repeat(b, int(gold["p8.workers_ok"]), 0), 1, p=8)
+    for p in (-1, 9):                                   # no such field width, however few the workers
+        with pytest.raises(orc.OracleError) as e:
+            orc.count_sign(b, 1, p=p)
+        assert e.value.code == orc.ERR_RANGE
+    with pytest.raises(orc.OracleError) as e:           # a vote needs a voter
+        orc.count_sign(np.ones((0, 3), np.uint8), 1)
+    assert e.value.code == orc.ERR_ARG
+
+
+def test_whole_step_range_rules():
+    """The p-bit step serves at most 2^p - 1 workers with p from 1 to 8 (Section 3's count of
+    bits); the level step needs the summed bytes level + L to fit a byte (Appendix F.1)."""
+    hp = dict(beta1=0.9, beta2=0.99, lr=1e-4, wd=0.1, step=1)
+
+    def pbit(W, p):
+        z = np.ones((W, 4), np.float32)
+        return orc.step_pbit(np.zeros(4, np.float32), z, z, p=p, **hp)
+
+    def l1(W, L):
+        z = np.zeros((W, 4), np.float32)
+        z[:, 0] = 1.0                                               # four times the mean: clamped to the top level
+        return orc.step_l1(np.zeros(4, np.float32), z, z, L=L, **hp)
+
+    for W, p in ((1, 1), (3, 2), (15, 4), (127, 7), (255, 8)):
+        assert pbit(W, p)["K"].tolist() == [W] * 4
+    for W, p in ((2, 1), (4, 2), (16, 4), (128, 7), (1, 0), (1, 9), (256, 9)):
+        with pytest.raises(orc.OracleError) as e:
+            pbit(W, p)
+        assert e.value.code == orc.ERR_RANGE
+    for W, L in ((8, 15), (1, 127), (127, 1), (5, 25)):
+        assert l1(W, L)["K"].tolist() == [2 * L * W] + [L * W] * 3  # bytes level + L: top level, then level 0
+    for W, L in ((9, 15), (2, 64), (128, 1), (64, 2)):
+        with pytest.raises(orc.OracleError) as e:
+            l1(W, L)
+        assert e.value.code == orc.ERR_RANGE
 
 
 @pytest.mark.parametrize("W", [4, 8, 16, 64])
@@ -555,3 +590,61 @@ def test_momentum_divergence_closed_forms():
     # averaging the momenta (Section 5) removes the divergence
     avg = orc.momentum_avg(m).astype(np.float32)
     assert orc.momentum_divergence(np.repeat(avg[None], 4, 0)) == 0.0
+    # the maximum may sit at either end of the range
+    for at in (0, 49):
+        m = np.zeros((4, 50), np.float32)
+        m[1, at] = 2.0
+        assert orc.momentum_divergence(m) == pytest.approx(math.sqrt(3) / 2, rel=1e-15)
+
+
+def test_oracle_loops_write_nothing_outside_their_outputs():
+    """Every C loop of the oracle is called on a ragged length with its outputs cut out of
+    larger arrays of a marker byte: the bytes on either side must keep the marker."""
+    n, W, guard, mark = 67, 3, 64, 0xA5
+    rng = np.random.default_rng(23)
+    checks = []
+
+    def out(count, dtype):
+        raw = np.full(count * np.dtype(dtype).itemsize + 2 * guard, mark, np.uint8)
+        checks.append((raw, count * np.dtype(dtype).itemsize))
+        return raw[guard:guard + count * np.dtype(dtype).itemsize].view(dtype)
+
+    ptr = orc._p
+    m = rng.standard_normal((W, n)).astype(np.float32)
+    g = rng.standard_normal((W, n)).astype(np.float32)
+    gb = (g.view(np.uint32) >> 16).astype(np.uint16)
+    nw = orc.n_words(n)
+    s = out(n, np.int8)
+    orc._local_sign(ptr(m[0]), ptr(g[0]), orc.F32, n, 0.9, ptr(s))
+    orc._local_sign_exact(ptr(m[0]), ptr(gb[0]), orc.BF16, n, 0.9, ptr(out(n, np.int8)))
+    b = out(n, np.uint8)
+    orc._zero_rule(ptr(s), n, 1, orc.ZERO_ALT, ptr(b))
+    words = out(nw, np.uint64)
+    orc._pack_1bit(ptr(b), n, ptr(words))
+    orc._unpack_1bit(ptr(words), n, ptr(out(n, np.uint8)))
+    for p in (2, 3, 4, 8):
+        fields = out(orc.field_bytes(n, p), np.uint8)
+        assert orc._pack_fields(ptr(b), n, p, ptr(fields)) == 0
+        assert orc._unpack_fields(ptr(fields), n, p, ptr(out(n, np.uint8))) == 0
+    bits = rng.integers(0, 2, (W, n)).astype(np.uint8)
+    u = out(n, np.int8)
+    assert orc._count_sign(ptr(bits), W, n, 0, 1, orc.TIE_ZERO, ptr(out(n, np.int32)), ptr(out(n, np.int32)), ptr(u)) == 0
+    pos, nz = out(nw, np.uint64), out(nw, np.uint64)
+    orc._planes(ptr(u), n, ptr(pos), ptr(nz))
+    orc._unplanes(ptr(pos), ptr(nz), n, ptr(out(n, np.int8)))
+    orc._apply(ptr(m[0]), ptr(u), n, 1e-4, 0.1, ptr(out(n, np.float64)))
+    orc._momentum(ptr(m[0]), ptr(g[0]), orc.F32, n, 0.99, ptr(out(n, np.float64)))
+    orc._momentum_avg(ptr(m), W, n, ptr(out(n, np.float64)))
+    orc._sum_bytes(ptr(bits), W, n, ptr(out(n, np.uint8)))
+    c = out(n, np.float32)
+    orc._local_c(ptr(m[0]), ptr(g[0]), orc.F32, n, 0.9, ptr(c))
+    orc._abs_totals(ptr(c), n, ptr(out(256, np.uint64)))
+    lev = out(n, np.int8)
+    orc._l1_levels(ptr(c), n, orc.mean_abs(c), 15, ptr(lev))
+    rows = (rng.integers(-15, 16, (W, n)) + 15).astype(np.uint8)
+    assert orc._level_sum_sign(ptr(rows), W, n, 15, 1, orc.TIE_ZERO, ptr(out(n, np.int32)), ptr(out(n, np.int32)), ptr(out(n, np.int8))) == 0
+    tern = rng.integers(-1, 2, (W, n)).astype(np.int8)
+    assert orc._ternary_vote(ptr(tern), W, n, ptr(out(n, np.int32)), ptr(out(n, np.int32)), ptr(out(n, np.int32)), ptr(out(n, np.int8))) == 0
+    assert len(checks) >= 30
+    for raw, size in checks:
+        assert np.all(raw[:guard] == mark) and np.all(raw[guard + size:] == mark)
