@@ -149,9 +149,11 @@ int lc_momentum_divergence_groups(const float *m, size_t m_stride_elems, int W, 
 
 /* Section 5 / 6.2, the policy the paper recommends: synchronise the momenta of selected
  * layers only, every `every` iterations (e.g. head and embedding, every 10).  If step is a
- * multiple of `every`, runs lc_momentum_avg on each range [offsets[r], offsets[r] +
- * sizes[r]) of the rows; otherwise does nothing.  offsets and sizes are HOST arrays of
- * n_ranges entries (element units; offsets multiples of 4); every >= 1. */
+ * multiple of `every`, every range [offsets[r], offsets[r] + sizes[r]) of the rows receives
+ * what lc_momentum_avg gives on it, bit for bit; otherwise nothing happens.  offsets and
+ * sizes are HOST arrays of n_ranges entries (element units; offsets multiples of 4; sizes
+ * may be 0), read before the call returns; every >= 1.  The ranges travel in the kernel
+ * arguments, 32 to a launch, and must not overlap: ranges of one launch run side by side. */
 int lc_momentum_sync_ranges(float *m, size_t m_stride_elems, int W, const size_t *offsets,
                             const size_t *sizes, int n_ranges, uint64_t step, uint64_t every,
                             void *stream);

@@ -23,7 +23,9 @@ LC_L1_STATIC_MAX_W = 64
 LC_MAX_GROUPS = 1 << 20
 LC_MAX_N = 1 << 38
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblioncub.so")
+# the in-tree build; LIONCUB_LIBRARY names another build of the same library (say one compiled
+# with different tuning macros) -- still the HIP library, there is no other implementation
+LIB_PATH = os.environ.get("LIONCUB_LIBRARY") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblioncub.so")
 
 _vp, _sz, _i, _u64, _f = C.c_void_p, C.c_size_t, C.c_int, C.c_uint64, C.c_float
 

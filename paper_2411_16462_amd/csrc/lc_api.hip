@@ -588,12 +588,7 @@ int lc_momentum_sync_ranges(float *m, size_t m_stride_elems, int W, const size_t
         if (sizes[r] > LC_MAX_N) return LC_ERR_SIZE;
     }
     if (step % every != 0 || W == 1) return LC_OK;  // not a synchronisation step
-    for (int r = 0; r < n_ranges; ++r) {
-        if (sizes[r] == 0) continue;
-        const hipError_t e = launch_momentum_avg(m + offsets[r], m_stride_elems, W, sizes[r], static_cast<hipStream_t>(stream));
-        if (e != hipSuccess) return from_hip(e);
-    }
-    return LC_OK;
+    return from_hip(launch_momentum_avg_ranges(m, m_stride_elems, W, offsets, sizes, n_ranges, static_cast<hipStream_t>(stream)));
 }
 
 int lc_vote_apply_1bit_groups(const uint64_t *q, size_t q_stride_words, int W, size_t n, uint64_t step, int tie_rule,

@@ -40,13 +40,14 @@ __device__ __forceinline__ void store4_guarded(float *p, size_t e, size_t n, f32
         if (e + k < n) st_stream(p + e + k, v[k]);
 }
 
+// the workgroup's tile: elements [block * 256, block * 256 + 256) of rows that hold n elements
 template <int R>
-__global__ __launch_bounds__(R *kWave) void momentum_avg_kernel(float *__restrict__ m, size_t stride, int W, size_t n, float inv_w)
+__device__ __forceinline__ void momentum_avg_tile(float *__restrict__ m, size_t stride, int W, size_t n, float inv_w, size_t block)
 {
     __shared__ f32x4 part[R][kWave];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = wave_index();
-    const size_t e = static_cast<size_t>(blockIdx.x) * kAvgTile + lane * 4;
+    const size_t e = block * kAvgTile + lane * 4;
     f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
     if (e < n) {
         int w = wave;
@@ -69,6 +70,37 @@ __global__ __launch_bounds__(R *kWave) void momentum_avg_kernel(float *__restric
     for (int w = wave; w < W; w += R) store4_guarded(m + static_cast<size_t>(w) * stride, e, n, mean);
 }
 
+template <int R>
+__global__ __launch_bounds__(R *kWave) void momentum_avg_kernel(float *__restrict__ m, size_t stride, int W, size_t n, float inv_w)
+{
+    momentum_avg_tile<R>(m, stride, W, n, inv_w, blockIdx.x);
+}
+
+// Several ranges of the rows in one launch (selective synchronisation, Section 6.2): the
+// ranges travel in the kernel arguments, workgroup b belongs to the range r with
+// first[r] <= b < first[r + 1] and handles that range's tile b - first[r] exactly as a
+// launch of its own on the range would.
+constexpr int kAvgRanges = 32;
+struct AvgRanges {
+    size_t off[kAvgRanges];         // first element of the range (a multiple of 4)
+    size_t size[kAvgRanges];        // its length in elements
+    uint32_t first[kAvgRanges + 1]; // running count of tiles
+    int count;
+};
+
+template <int R>
+__global__ __launch_bounds__(R *kWave) void momentum_avg_ranges_kernel(float *__restrict__ m, size_t stride, int W, float inv_w,
+                                                                       const AvgRanges ranges)
+{
+    int lo = 0, hi = ranges.count - 1;  // uniform bisection over at most 32 entries
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (ranges.first[mid] <= blockIdx.x) lo = mid;
+        else hi = mid - 1;
+    }
+    momentum_avg_tile<R>(m + ranges.off[lo], stride, W, ranges.size[lo], inv_w, blockIdx.x - ranges.first[lo]);
+}
+
 hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStream_t s)
 {
     const unsigned grid = static_cast<unsigned>((n + kAvgTile - 1) / kAvgTile);
@@ -76,6 +108,40 @@ hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStre
     if (W >= 8) return launch(momentum_avg_kernel<8>, grid, 8 * kWave, LC_AVG_LDS, s, m, stride, W, n, inv_w);
     if (W >= 4) return launch(momentum_avg_kernel<4>, grid, 4 * kWave, 0, s, m, stride, W, n, inv_w);
     return launch(momentum_avg_kernel<2>, grid, 2 * kWave, 0, s, m, stride, W, n, inv_w);
+}
+
+// Ranges in batches of kAvgRanges per launch; empty ranges are skipped.  A batch also ends
+// before its tile count would pass 32 bits.
+hipError_t launch_momentum_avg_ranges(float *m, size_t stride, int W, const size_t *offsets, const size_t *sizes, int n_ranges,
+                                      hipStream_t s)
+{
+    const float inv_w = 1.0f / static_cast<float>(W);
+    int r = 0;
+    while (r < n_ranges) {
+        AvgRanges batch;
+        batch.count = 0;
+        uint64_t tiles = 0;
+        for (; r < n_ranges && batch.count < kAvgRanges; ++r) {
+            if (sizes[r] == 0) continue;
+            const uint64_t t = (sizes[r] + kAvgTile - 1) / kAvgTile;
+            if (tiles + t > 0xFFFFFFFFull) break;
+            batch.off[batch.count] = offsets[r];
+            batch.size[batch.count] = sizes[r];
+            batch.first[batch.count] = static_cast<uint32_t>(tiles);
+            tiles += t;
+            ++batch.count;
+        }
+        if (batch.count == 0) continue;  // only empty ranges were left
+        for (int k = batch.count; k < kAvgRanges; ++k) batch.off[k] = batch.size[k] = 0;
+        for (int k = batch.count; k <= kAvgRanges; ++k) batch.first[k] = static_cast<uint32_t>(tiles);
+        const unsigned grid = static_cast<unsigned>(tiles);
+        hipError_t e;
+        if (W >= 8) e = launch(momentum_avg_ranges_kernel<8>, grid, 8 * kWave, LC_AVG_LDS, s, m, stride, W, inv_w, batch);
+        else if (W >= 4) e = launch(momentum_avg_ranges_kernel<4>, grid, 4 * kWave, 0, s, m, stride, W, inv_w, batch);
+        else e = launch(momentum_avg_ranges_kernel<2>, grid, 2 * kWave, 0, s, m, stride, W, inv_w, batch);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // ---- divergence of the workers' momenta (Section 5.1, the quantity of Figure 6) --------

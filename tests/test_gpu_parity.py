@@ -444,6 +444,41 @@ def test_momentum_sync_ranges_policy():
     assert np.array_equal(got[:, ~inside], case.m0[:, ~inside])              # everything else untouched
 
 
+@pytest.mark.parametrize("W,n_ranges", [(2, 5), (4, 32), (8, 33), (16, 100), (3, 70)])
+def test_momentum_sync_many_ranges(W, n_ranges):
+    """Selective synchronisation over more ranges than one launch carries: ranges of 0 to
+    3000 elements (lengths that are no multiple of 4, empty ones, one longer than a few
+    tiles) with gaps between them.  Every range equals lc_momentum_avg on that range bit for
+    bit and the oracle within tolerance; the gaps keep their values."""
+    rng = np.random.default_rng(15100 + W + n_ranges)
+    offsets, sizes, at = [], [], 0
+    for r in range(n_ranges):
+        at += 4 * int(rng.integers(0, 40))
+        sz = int(rng.choice([0, 1, 3, 4, 255, 256, 257, 1000, 3000, 70001])) if r % 7 else int(rng.integers(0, 3000))
+        offsets.append(at)
+        sizes.append(sz)
+        at += (sz + 3) // 4 * 4
+    n = at + 64
+    case = Case(n, W, seed=15200 + W, m_spread=1.0)
+    twin = clone_rows(case.m)
+    lc.lc_momentum_sync_ranges(case.m, case.m.stride(0), W, offsets, sizes, n_ranges, 30, 10)
+    for o, sz in zip(offsets, sizes):
+        if sz:
+            lc.lc_momentum_avg(twin[:, o:], twin.stride(0), W, sz)
+    torch.cuda.synchronize()
+    got = case.m.cpu().numpy()
+    assert np.array_equal(got, twin.cpu().numpy())                           # one launch per batch == one launch per range
+    inside = np.zeros(n, bool)
+    for o, sz in zip(offsets, sizes):
+        inside[o:o + sz] = True
+        if sz:
+            ref = orc.momentum_avg(case.m0[:, o:o + sz])
+            for w in range(W):
+                assert_close(got[w, o:o + sz], ref, "averaged range")
+    assert np.array_equal(got[:, ~inside], case.m0[:, ~inside])
+    assert inside.sum() > 0 and (~inside).sum() > 0
+
+
 def test_hip_graph_replay_matches_eager():
     """The library only launches kernels (no memsets, no allocation, no synchronisation),
     so a step can be captured into a HIP graph.  Several replays, with eager work and
