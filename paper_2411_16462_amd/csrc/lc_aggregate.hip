@@ -671,6 +671,67 @@ __global__ __launch_bounds__(kVoteThreads) void vote_only_kernel(const AggParams
     if (P.vote_nz) P.vote_nz[jw] = nz & vm;
 }
 
+// The same for the ternary wire format (Appendix B.1): row w is a pair of words, pos and nz;
+// pos & nz are the votes for +1, nz & ~pos the votes for -1, counted in two sets of planes
+// and compared plane by plane.  K+ == K- is a zero of the vote, whatever W is.
+__device__ __forceinline__ void vote_load8_ternary(uint64_t (&plus)[8], uint64_t (&minus)[8], const uint64_t *pos, const uint64_t *nz,
+                                                   size_t stride)
+{
+    uint64_t p[8], z[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        p[i] = ld_packed(pos + static_cast<size_t>(i) * stride);
+        z[i] = ld_packed(nz + static_cast<size_t>(i) * stride);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        plus[i] = p[i] & z[i];
+        minus[i] = z[i] & ~p[i];
+    }
+}
+
+template <bool WHOLE8>
+__global__ __launch_bounds__(kVoteThreads) void vote_only_ternary_kernel(const AggParams P)
+{
+    const size_t jw = static_cast<size_t>(blockIdx.x) * kVoteThreads + threadIdx.x;
+    const size_t n = P.n;
+    if (jw * 64 >= n) return;
+    const int W = P.W;
+    const size_t stride = P.q_stride_bytes / 8;
+    const uint64_t *pcur = static_cast<const uint64_t *>(P.q) + jw;
+    const uint64_t *zcur = static_cast<const uint64_t *>(P.q2) + jw;
+    uint64_t cp[8] = {0, 0, 0, 0, 0, 0, 0, 0}, cn[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if constexpr (WHOLE8) {  // W is a multiple of 8: sixteen straight-line loads per step
+        for (int w = 0; w < W; w += 8) {
+            uint64_t plus[8], minus[8];
+            vote_load8_ternary(plus, minus, pcur + static_cast<size_t>(w) * stride, zcur + static_cast<size_t>(w) * stride, stride);
+            csa8(cp, plus);
+            csa8(cn, minus);
+        }
+    } else {
+        for (int w = 0; w < W; w += 8) {
+            uint64_t plus[8], minus[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint64_t pw = (w + i < W) ? ld_packed(pcur + static_cast<size_t>(w + i) * stride) : 0ull;
+                const uint64_t zw = (w + i < W) ? ld_packed(zcur + static_cast<size_t>(w + i) * stride) : 0ull;
+                plus[i] = pw & zw;
+                minus[i] = zw & ~pw;
+            }
+            csa8(cp, plus);
+            csa8(cn, minus);
+        }
+    }
+    const uint64_t vm = valid_mask(jw * 64, n);
+    uint64_t gt, eq;
+    compare_two(cp, cn, gt, eq);
+    if (P.vote_pos) P.vote_pos[jw] = gt & vm;
+    if (P.vote_nz) P.vote_nz[jw] = ~eq & vm;
+}
+
+#ifndef LC_VOTE_TERNARY
+#define LC_VOTE_TERNARY 1
+#endif
 static hipError_t launch_vote_only(const AggParams &P, hipStream_t s)
 {
     const size_t nw = (P.n + 63) / 64;
@@ -1006,7 +1067,14 @@ hipError_t launch_aggregate(const AggParams &P, int in_kind, bool apply, bool ko
     case IN_BITS:
         if (!apply && !kout) return launch_vote_only(P, s);
         return kout ? launch_in<IN_BITS, true>(P, apply, g_dtype, s) : launch_in<IN_BITS, false>(P, apply, g_dtype, s);
-    case IN_TERNARY: return launch_in<IN_TERNARY, false>(P, apply, g_dtype, s);
+    case IN_TERNARY:
+        if (LC_VOTE_TERNARY && !apply) {
+            const size_t nw = (P.n + 63) / 64;
+            const unsigned grid = static_cast<unsigned>((nw + kVoteThreads - 1) / kVoteThreads);
+            if (P.W % 8 == 0) return launch(vote_only_ternary_kernel<true>, grid, kVoteThreads, LC_VOTE_LDS, s, P);
+            return launch(vote_only_ternary_kernel<false>, grid, kVoteThreads, LC_VOTE_LDS, s, P);
+        }
+        return launch_in<IN_TERNARY, false>(P, apply, g_dtype, s);
     case 2: return launch_in<2, false>(P, apply, g_dtype, s);
     case 4: return launch_in<4, false>(P, apply, g_dtype, s);
     default: return launch_in<8, false>(P, apply, g_dtype, s);
