@@ -751,7 +751,40 @@ static hipError_t launch_vote_only(const AggParams &P, hipStream_t s)
 #endif
 constexpr int kApplyThreads = 64;
 
-template <int GDT, bool MOM>
+// u of the lane's elements e .. e + left - 1.  IN = 0: from the two planes (byte e / 8 of each,
+// the lane's nibble).  IN = 2, 4, 8: from one buffer of counts in IN-bit fields (what a summing
+// allreduce leaves), u = sign of K against the threshold.
+template <int IN>
+__device__ __forceinline__ void apply_signs(const AggParams &P, size_t e, int left, int lane, float (&uf)[4])
+{
+    if constexpr (IN == 0) {
+        const uint8_t *pos8 = reinterpret_cast<const uint8_t *>(P.in_pos);
+        const uint8_t *nz8 = reinterpret_cast<const uint8_t *>(P.in_nz);
+        const uint32_t sh = (lane & 1) * 4;
+        const uint32_t pn = static_cast<uint32_t>(pos8[e / 8]) >> sh;
+        const uint32_t zn = nz8 ? static_cast<uint32_t>(nz8[e / 8]) >> sh : 0xFu;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) uf[k] = ((zn >> k) & 1u) ? (((pn >> k) & 1u) ? 1.0f : -1.0f) : 0.0f;
+    } else {
+        const uint8_t *src = static_cast<const uint8_t *>(P.q) + e * IN / 8;
+        uint32_t x = 0;
+        if (left == 4) {
+            if (IN == 8) x = *reinterpret_cast<const uint32_t *>(src);
+            else if (IN == 4) x = *reinterpret_cast<const uint16_t *>(src);
+            else x = *src;
+        } else {
+            for (int b = 0; b < (left * IN + 7) / 8; ++b) x |= static_cast<uint32_t>(src[b]) << (8 * b);
+        }
+        const float tie_u = !P.tie_possible ? -1.0f : (P.tie < 0 ? 0.0f : (P.tie > 0 ? 1.0f : -1.0f));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int K = static_cast<int>((x >> (IN * k)) & ((1u << IN) - 1u));
+            uf[k] = K > P.thresh ? 1.0f : (K == P.thresh ? tie_u : -1.0f);
+        }
+    }
+}
+
+template <int GDT, bool MOM, int IN>
 __global__ __launch_bounds__(kApplyThreads) void apply_only_kernel(const AggParams P)
 {
     const int lane = threadIdx.x;
@@ -762,9 +795,6 @@ __global__ __launch_bounds__(kApplyThreads) void apply_only_kernel(const AggPara
     const size_t r = blockIdx.y;
     float *mrow = MOM ? P.m + r * P.m_stride : nullptr;
     const void *grow = MOM ? static_cast<const char *>(P.g) + r * P.g_stride * Grad<GDT>::kBytes : nullptr;
-    const uint8_t *pos8 = reinterpret_cast<const uint8_t *>(P.in_pos);
-    const uint8_t *nz8 = reinterpret_cast<const uint8_t *>(P.in_nz);
-    const uint32_t sh = (lane & 1) * 4;
 
     if (tile + 256 <= n) {
         f32x4 th = {0.0f, 0.0f, 0.0f, 0.0f}, mv = th, gv = th;
@@ -774,13 +804,10 @@ __global__ __launch_bounds__(kApplyThreads) void apply_only_kernel(const AggPara
             gv = Grad<GDT>::load4(grow, e);
         }
         if (r == 0) {
-            const uint32_t pn = static_cast<uint32_t>(pos8[e / 8]) >> sh;
-            const uint32_t zn = nz8 ? static_cast<uint32_t>(nz8[e / 8]) >> sh : 0xFu;
+            float uf[4];
+            apply_signs<IN>(P, e, 4, lane, uf);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const float uf = ((zn >> k) & 1u) ? (((pn >> k) & 1u) ? 1.0f : -1.0f) : 0.0f;
-                th[k] = __builtin_fmaf(-P.lr, __builtin_fmaf(P.wd, th[k], uf), th[k]);
-            }
+            for (int k = 0; k < 4; ++k) th[k] = __builtin_fmaf(-P.lr, __builtin_fmaf(P.wd, th[k], uf[k]), th[k]);
             store4(P.theta + e, th);
         }
         if (MOM) {
@@ -791,24 +818,25 @@ __global__ __launch_bounds__(kApplyThreads) void apply_only_kernel(const AggPara
         return;
     }
     if (e >= n) return;
-    const uint32_t pn = static_cast<uint32_t>(pos8[e / 8]) >> sh;
-    const uint32_t zn = nz8 ? static_cast<uint32_t>(nz8[e / 8]) >> sh : 0xFu;
-    for (int k = 0; k < 4 && e + k < n; ++k) {
+    const int left = n - e >= 4 ? 4 : static_cast<int>(n - e);
+    float uf[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (r == 0) apply_signs<IN>(P, e, left, lane, uf);
+    for (int k = 0; k < left; ++k) {
         if (r == 0) {
-            const float uf = ((zn >> k) & 1u) ? (((pn >> k) & 1u) ? 1.0f : -1.0f) : 0.0f;
             const float v = P.theta[e + k];
-            P.theta[e + k] = __builtin_fmaf(-P.lr, __builtin_fmaf(P.wd, v, uf), v);
+            P.theta[e + k] = __builtin_fmaf(-P.lr, __builtin_fmaf(P.wd, v, uf[k]), v);
         }
         if (MOM) mrow[e + k] = momentum_step(mrow[e + k], Grad<GDT>::load1(grow, e + k), P.beta2, P.omb2);
     }
 }
 
+template <int IN>
 static hipError_t launch_apply_only(const AggParams &P, int g_dtype, hipStream_t s)
 {
     const dim3 grid(static_cast<unsigned>((P.n + 255) / 256), static_cast<unsigned>(P.n_m > 0 ? P.n_m : 1));
-    if (P.n_m == 0) return launch(apply_only_kernel<LC_F32, false>, grid, kApplyThreads, LC_APPLY_LDS, s, P);
-    if (g_dtype == LC_BF16) return launch(apply_only_kernel<LC_BF16, true>, grid, kApplyThreads, LC_APPLY_LDS, s, P);
-    return launch(apply_only_kernel<LC_F32, true>, grid, kApplyThreads, LC_APPLY_LDS, s, P);
+    if (P.n_m == 0) return launch(apply_only_kernel<LC_F32, false, IN>, grid, kApplyThreads, LC_APPLY_LDS, s, P);
+    if (g_dtype == LC_BF16) return launch(apply_only_kernel<LC_BF16, true, IN>, grid, kApplyThreads, LC_APPLY_LDS, s, P);
+    return launch(apply_only_kernel<LC_F32, true, IN>, grid, kApplyThreads, LC_APPLY_LDS, s, P);
 }
 
 // Aggregate + apply for few workers, one 256-element tile per wave (no momentum streams).
@@ -1060,9 +1088,16 @@ hipError_t launch_aggregate(const AggParams &P, int in_kind, bool apply, bool ko
         if (in_kind == 4) return launch_tile<4, false>(P, s);
         return launch_tile<8, false>(P, s);
     }
+    // one buffer of counts and momentum rows to update: a row per grid line, as from planes
+    if (LC_APPLY_ONLY && apply && P.W == 1 && P.n_m > 0 && P.n_seg == 0 && !P.vote_pos && !P.vote_nz && !P.sum_out &&
+        (in_kind == 2 || in_kind == 4 || in_kind == 8)) {
+        if (in_kind == 2) return launch_apply_only<2>(P, g_dtype, s);
+        if (in_kind == 4) return launch_apply_only<4>(P, g_dtype, s);
+        return launch_apply_only<8>(P, g_dtype, s);
+    }
     switch (in_kind) {
     case IN_PLANES:
-        if (LC_APPLY_ONLY && apply && P.n_seg == 0 && !P.vote_pos && !P.vote_nz) return launch_apply_only(P, g_dtype, s);
+        if (LC_APPLY_ONLY && apply && P.n_seg == 0 && !P.vote_pos && !P.vote_nz) return launch_apply_only<0>(P, g_dtype, s);
         return launch_in<IN_PLANES, false>(P, apply, g_dtype, s);
     case IN_BITS:
         if (!apply && !kout) return launch_vote_only(P, s);
