@@ -88,6 +88,35 @@ def test_l1_dynamic_range(g_dtype, spread):
     assert (ref["levels"] != 0).any() and np.abs(ref["levels"]).max() == L
 
 
+@pytest.mark.parametrize("W,L", [(2, 15), (8, 3), (5, 25)])
+@pytest.mark.parametrize("tie", [lc.LC_TIE_ZERO, lc.LC_TIE_ALT])
+@pytest.mark.parametrize("step", [1, 2, 7])
+def test_level_sum_tie_rules(W, L, tie, step):
+    """Level rows that tie often (small symmetric levels): the sign of the summed levels with
+    both tie rules on odd and even iterations, sums and planes out and applied."""
+    n = 70001
+    rng = np.random.default_rng(23000 + W + L + step)
+    levels = rng.integers(-1, 2, (W, n)) * rng.integers(0, L + 1, (W, n))
+    levels[:, 500:900] = 0                                                # whole columns of zeros: ties whatever W is
+    fields = (levels + L).astype(np.uint8)
+    K, S, u = orc.level_sum_sign(fields, L, step, tie)
+    assert (S == 0).sum() > 400 and (S > 0).any() and (S < 0).any()
+    assert ((u == 0) == (S == 0)).all() if tie == lc.LC_TIE_ZERO else (u != 0).all()
+    case = Case(n, W, seed=23100 + W)
+    q = guarded(W, n, "cuda")
+    q[:, :n] = torch.from_numpy(fields).cuda()
+    nw = (n + 63) // 64
+    ksum, pos, nz = guarded(1, n, "cuda"), guarded(1, nw * 8, "cuda"), guarded(1, nw * 8, "cuda")
+    lc.lc_level_sum_sign(q, q.stride(0), W, n, L, ksum, pos, nz, step, tie)
+    lc.lc_level_sum_apply(q, q.stride(0), W, n, L, None, step, tie, case.theta, HP["lr"], HP["wd"], None, 0, None, 0,
+                          lc.LC_F32, 0, HP["beta2"])
+    torch.cuda.synchronize()
+    assert np.array_equal(ksum[0, :n].cpu().numpy().astype(np.int32), K), "summed level bytes"
+    got_u = orc.unplanes(words_of(pos, nw)[0], words_of(nz, nw)[0], n)
+    assert np.array_equal(got_u, u), "planes of the sign"
+    assert_close(case.theta.cpu().numpy(), orc.apply(case.theta0, u, HP["lr"], HP["wd"]), "theta")
+
+
 def test_l1_all_zero_and_empty():
     n, W, L = 5000, 2, 15
     case = Case(n, W, seed=22000, m_scale=0.0)

@@ -87,6 +87,36 @@ def test_1bit_rules_and_dtypes(g_dtype, zero, tie, step):
     check_1bit(out, ref)
 
 
+@pytest.mark.parametrize("p,W", [(2, 2), (4, 8), (8, 6)])
+@pytest.mark.parametrize("zero", [lc.LC_ZERO_ALT, lc.LC_ZERO_POS, lc.LC_ZERO_NEG])
+@pytest.mark.parametrize("tie", [lc.LC_TIE_ZERO, lc.LC_TIE_ALT])
+@pytest.mark.parametrize("step", [1, 2])
+def test_pbit_rules(p, W, zero, tie, step):
+    """Every zero rule and tie rule on odd and even iterations through the field path: exact
+    zeros of c in whole columns and for single workers, an even worker count so that ties occur."""
+    n = 12345
+    C = lc.lc_container_bits(p)
+    case = Case(n, W, seed=3100 + p, m_scale=0.0)
+    case.g[:, 100:300] = 0
+    case.g[1, 5000:5100] = 0
+    case.g[:, n - 7:] = 0
+    case.snapshot()
+    ref = oracle_step(case, HP, step, zero, tie, p=p)
+    assert (ref["s"][:, 100:300] == 0).all() and (ref["S"] == 0).any()
+    q, nbytes = hip_update_pack(case, HP, step, C, zero)
+    assert np.array_equal(q[:, :nbytes].cpu().numpy(), ref["fields"]), "p-bit fields"
+    nw, fb = nwords(n), (n * C + 7) // 8
+    sum_out = guarded(1, fb, case.device)
+    pos, nz = guarded(1, nw * 8, case.device), guarded(1, nw * 8, case.device)
+    lc.lc_pbit_sum_sign(q, q.stride(0), C, W, n, p, sum_out, pos, nz, step, tie)
+    lc.lc_pbit_sum_apply(q, q.stride(0), C, W, n, p, None, step, tie, case.theta, HP["lr"], HP["wd"], None, 0, None, 0,
+                         lc.LC_F32, 0, HP["beta2"])
+    torch.cuda.synchronize()
+    assert np.array_equal(sum_out[0, :fb].cpu().numpy(), ref["sum_fields"]), "field sums"
+    assert np.array_equal(words_of(pos, nw)[0], ref["pos"]) and np.array_equal(words_of(nz, nw)[0], ref["nz"])
+    assert_close(case.theta.cpu().numpy(), ref["theta"], "theta")
+
+
 def test_special_values():
     """NaN, infinities, signed zeros, denormals and exact cancellation in c."""
     n, W = 4096 + 64, 3
