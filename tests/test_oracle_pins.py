@@ -108,6 +108,12 @@ def test_bit_budget_from_paper():
     with pytest.raises(orc.OracleError) as e:           # a vote needs a voter
         orc.count_sign(np.ones((0, 3), np.uint8), 1)
     assert e.value.code == orc.ERR_ARG
+    for call in (lambda: orc.level_sum_sign(np.zeros((0, 3), np.uint8), 15, 1),
+                 lambda: orc.level_sum_sign(np.zeros((2, 3), np.uint8), 0, 1),
+                 lambda: orc.ternary_vote(np.zeros((0, 3), np.int8))):
+        with pytest.raises(orc.OracleError) as e:
+            call()
+        assert e.value.code == orc.ERR_ARG
 
 
 def test_whole_step_range_rules():
@@ -600,7 +606,12 @@ def test_momentum_divergence_closed_forms():
 def test_oracle_loops_write_nothing_outside_their_outputs():
     """Every C loop of the oracle is called on a ragged length with its outputs cut out of
     larger arrays of a marker byte: the bytes on either side must keep the marker."""
-    n, W, guard, mark = 67, 3, 64, 0xA5
+    for n in (67, 64 * 63):
+        _guard_band_pass(n)
+
+
+def _guard_band_pass(n):
+    W, guard, mark = 3, 64, 0xA5
     rng = np.random.default_rng(23)
     checks = []
 
@@ -638,7 +649,11 @@ def test_oracle_loops_write_nothing_outside_their_outputs():
     orc._sum_bytes(ptr(bits), W, n, ptr(out(n, np.uint8)))
     c = out(n, np.float32)
     orc._local_c(ptr(m[0]), ptr(g[0]), orc.F32, n, 0.9, ptr(c))
-    orc._abs_totals(ptr(c), n, ptr(out(256, np.uint64)))
+    totals = out(256, np.uint64)                           # arrives full of the marker: the function clears it itself
+    orc._abs_totals(ptr(c), n, ptr(totals))
+    clean = np.zeros(256, np.uint64)
+    orc._abs_totals(ptr(c), n, ptr(clean))
+    assert np.array_equal(totals, clean) and clean.sum() > 0
     lev = out(n, np.int8)
     orc._l1_levels(ptr(c), n, orc.mean_abs(c), 15, ptr(lev))
     rows = (rng.integers(-15, 16, (W, n)) + 15).astype(np.uint8)
