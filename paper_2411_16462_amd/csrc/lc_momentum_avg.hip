@@ -111,7 +111,7 @@ hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStre
 }
 
 // Ranges in batches of kAvgRanges per launch; empty ranges are skipped.  A batch also ends
-// before its tile count would pass 32 bits.
+// before its tile count would pass what one grid holds.
 hipError_t launch_momentum_avg_ranges(float *m, size_t stride, int W, const size_t *offsets, const size_t *sizes, int n_ranges,
                                       hipStream_t s)
 {
@@ -124,7 +124,7 @@ hipError_t launch_momentum_avg_ranges(float *m, size_t stride, int W, const size
         for (; r < n_ranges && batch.count < kAvgRanges; ++r) {
             if (sizes[r] == 0) continue;
             const uint64_t t = (sizes[r] + kAvgTile - 1) / kAvgTile;
-            if (tiles + t > 0xFFFFFFFFull) break;
+            if (tiles + t > 0x7FFFFFFFull) break;  // a grid holds 2^31 - 1 workgroups
             batch.off[batch.count] = offsets[r];
             batch.size[batch.count] = sizes[r];
             batch.first[batch.count] = static_cast<uint32_t>(tiles);
