@@ -1,6 +1,10 @@
 """Randomised differential test: many seeded random configurations (sizes, worker counts,
 rules, dtypes, hyper-parameters, input regimes) through every path of the library,
-each against the oracle.  Deterministic: the configurations come from one fixed seed."""
+each against the oracle.  Deterministic: the configurations come from one fixed seed.
+For a longer campaign LIONCUB_RANDOM_SCALE multiplies the number of configurations and
+LIONCUB_RANDOM_SEED shifts the seeds (both default to the committed set)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -13,7 +17,8 @@ pytestmark = pytest.mark.gpu
 
 
 def configs(count, seed):
-    rng = np.random.default_rng(seed)
+    count *= int(os.environ.get("LIONCUB_RANDOM_SCALE", "1"))
+    rng = np.random.default_rng(seed + int(os.environ.get("LIONCUB_RANDOM_SEED", "0")))
     out = []
     for i in range(count):
         n = int(rng.choice([rng.integers(1, 300), rng.integers(300, 5000), rng.integers(5000, 70000)]))
