@@ -530,8 +530,14 @@ def test_hip_graph_replay_matches_eager():
                           stream=stream)                      # zeroes its workspace with a kernel, not a memset
         lc.lc_l1_quantize_pack(case.g, case.g.stride(0), case.gd, case.m, case.m.stride(0), W, n, HP["beta1"], 0,
                                HP["beta2"], 15, mean, lv, lv.stride(0), stream=stream)
-        lc.lc_momentum_avg(case.m, case.m.stride(0), W, n, stream=stream)
+        lc.lc_momentum_divergence(case.m, case.m.stride(0), W, n, div, stream=stream)   # clears its slot with a kernel too
+        lc.lc_momentum_divergence_groups(case.m, case.m.stride(0), W, n, ends, 3, divg, stream=stream)
+        lc.lc_momentum_sync_ranges(case.m, case.m.stride(0), W, [0, 4096, 70000], [1000, 30001, 64], 3, 10, 5, stream=stream)
+        lc.lc_momentum_avg(case.m[:, 100000:], case.m.stride(0), W, n - 100000, stream=stream)
 
+    div = torch.zeros(1, dtype=torch.float64, device="cuda")
+    divg = torch.zeros(3, dtype=torch.float64, device="cuda")
+    ends = torch.tensor([100, 2000, (n + 63) // 64], dtype=torch.int32, device="cuda")
     qe, qg = guarded(W, nw * 8, "cuda"), guarded(W, nw * 8, "cuda")
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -548,11 +554,15 @@ def test_hip_graph_replay_matches_eager():
         step(eager, qe, None)
         lv_eager = lv.clone()
         mean_eager = mean.clone()
+        div_eager, divg_eager = div.clone(), divg.clone()
         torch.cuda.synchronize()
         lv.zero_()
         mean.zero_()
+        div.fill_(-1.0)
+        divg.fill_(-1.0)
         g.replay()
         torch.cuda.synchronize()
+        assert div_eager.item() > 0 and torch.equal(div, div_eager) and torch.equal(divg, divg_eager), "replay %d: divergence" % replay
         assert torch.equal(qe, qg), "replay %d: packed words" % replay
         assert torch.equal(eager.theta, graph.theta) and torch.equal(eager.m, graph.m), "replay %d" % replay
         assert torch.equal(lv, lv_eager) and torch.equal(mean, mean_eager), "replay %d: L1 levels" % replay
