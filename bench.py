@@ -74,6 +74,8 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (for odd and for even iterations) into HIP graphs and time replays; "
                          "per-kernel timings are then not available and the roofline entry is for the whole step")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the bare streaming kernels (lc_stream_probe) that give the `ceilings` entry")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="also run one plain device copy of BYTES (read BYTES, write BYTES) before the steps: "
                          "the reference point for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -368,6 +370,30 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
 
 
 
+def ceilings(torch, lc, n=(1 << 29) + 4160, reps=10):
+    """What bare streaming kernels of the library's own shape reach on this device, measured in this run
+    (lc_stream_probe on two buffers of n floats): context for the roofline fractions, which stay against the
+    published peak.  Median of `reps` launches each, GB/s."""
+    a = torch.randn(n, device="cuda")
+    b = torch.randn(n, device="cuda")
+    kinds = (("read", lc.LC_PROBE_READ, 4), ("write", lc.LC_PROBE_WRITE, 4), ("copy", lc.LC_PROBE_COPY, 8),
+             ("scale_in_place", lc.LC_PROBE_SCALE, 8), ("read2_write1", lc.LC_PROBE_RMW2, 12))
+    out = {"unit": "GB/s", "floats_per_buffer": n, "launches": reps}
+    for name, kind, per in kinds:
+        ts = []
+        for i in range(reps + 3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            lc.lc_stream_probe(kind, a, b, n, 1.0)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        out[name] = per * n / (stats(ts[3:])["median"] * 1e-3) / 1e9
+    del a, b
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(wl, st, torch, sample, sample_single, threads):
     """The oracle, as it stands, on the first parameters of the same buffers: once on one
     thread (the first `sample_single` parameters) and once split into contiguous chunks over
@@ -570,6 +596,7 @@ def main():
     wl = synth.workload(args.workload)
     if args.divergence and wl.mode == "prepacked":
         sys.exit("bench.py: --divergence needs a workload with one momentum row per worker (c0 .. c3, l1, t2)")
+    ceil = None if args.no_ceilings else ceilings(torch, lc)
     build_kw = dict(per_tensor=args.per_tensor, groups=args.groups, split=args.split,
                     variant="sum" if args.sum else "vote", one_plane=args.one_plane, divergence=args.divergence)
     run = Run(wl, torch, lc, synth, 1 if args.graph else args.copies, **build_kw)
@@ -637,6 +664,12 @@ def main():
         "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": roofline, "kernels": per_kernel,
     }
+    if ceil is not None:
+        # the bare kernel nearest to the dominant kernel's mix of reads and writes
+        kind = "read2_write1" if "update_pack" in dom["kernel"] or "quantize" in dom["kernel"] else "copy"
+        out["ceilings"] = ceil
+        roofline.update(measured_ceiling=ceil[kind], measured_ceiling_kind=kind + " (lc_stream_probe, this run)",
+                        frac_of_measured_ceiling=dom["achieved_GBps"] / ceil[kind])
     if args.cpu_sample > 0:
         out["cpu_baseline"] = cpu_baseline(wl, run.sets[0][1], torch, args.cpu_sample, args.cpu_sample_single,
                                            args.cpu_threads)

@@ -320,9 +320,22 @@ int lc_level_sum_apply_groups(const uint8_t *q, size_t q_stride_bytes, int W, si
                               const float *group_lr, const float *group_wd, int n_groups,
                               void *stream);
 
-/* ---- Utilities (host only; they follow no passage of the paper) ------------------------
+/* ---- Utilities (they follow no passage of the paper) -----------------------------------
  * lc_container_bits, lc_status_string, lc_version and lc_l1_groups_workspace_words above
- * touch no device memory and launch nothing. */
+ * touch no device memory and launch nothing; lc_stream_probe launches one bare streaming
+ * kernel, a calibration aid for measurements. */
+
+/* What this device reaches when a kernel only moves data, in the shape of the library's
+ * streaming kernels (one wave per 256-element tile, 16-byte non-temporal accesses).  a and b
+ * are device arrays of n floats, 16-byte aligned, not overlapping.  kind: */
+#define LC_PROBE_READ 0   /* reads a, writes nothing                       4 n bytes */
+#define LC_PROBE_WRITE 1  /* a[i] = s                                      4 n bytes */
+#define LC_PROBE_COPY 2   /* a[i] = b[i]                                   8 n bytes */
+#define LC_PROBE_SCALE 3  /* a[i] = a[i] * s, in place                     8 n bytes */
+#define LC_PROBE_RMW2 4   /* a[i] = fma(s, a[i], fl(fl(1 - s) * b[i])): two streams read, one of
+                             them written in place, update+pack without the packing  12 n bytes */
+/* b may be NULL for READ, WRITE and SCALE.  Errors as for the other calls. */
+int lc_stream_probe(int kind, float *a, const float *b, size_t n, float s, void *stream);
 
 /* Smallest field width of 1, 2, 4, 8 bits that holds a p-bit value (the container rule of
  * the p-bit layout above); -1 if p is not in 1..8. */

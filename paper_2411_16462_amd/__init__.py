@@ -17,6 +17,7 @@ LC_OK, LC_ERR_NULL, LC_ERR_SIZE, LC_ERR_ALIGN, LC_ERR_RANGE, LC_ERR_DTYPE, LC_ER
 LC_F32, LC_BF16 = 0, 1
 LC_ZERO_ALT, LC_ZERO_POS, LC_ZERO_NEG = 0, 1, 2
 LC_TIE_ZERO, LC_TIE_ALT = 0, 1
+LC_PROBE_READ, LC_PROBE_WRITE, LC_PROBE_COPY, LC_PROBE_SCALE, LC_PROBE_RMW2 = 0, 1, 2, 3, 4
 LC_MAX_W = 255
 LC_L1_WORKSPACE_WORDS = 384
 LC_L1_STATIC_MAX_W = 64
@@ -60,6 +61,7 @@ SIGNATURES = {
     "lc_level_sum_apply": (_i, [_vp, _sz, _i, _sz, _i, _vp, _u64, _i, _vp, _f, _f, _vp, _sz, _vp, _sz, _i, _i, _f, _vp]),
     "lc_container_bits": (_i, [_i]),
     "lc_status_string": (C.c_char_p, [_i]),
+    "lc_stream_probe": (_i, [_i, _vp, _vp, _sz, _f, _vp]),
     "lc_version": (_i, []),
 }
 
@@ -273,6 +275,10 @@ def lc_container_bits(p):
 
 def lc_status_string(status):
     return load().lc_status_string(status).decode()
+
+
+def lc_stream_probe(kind, a, b, n, s, stream=None, check=True):
+    return _call("lc_stream_probe", check, kind, _ptr(a), _ptr(b), n, s, _stream(stream))
 
 
 def lc_version():

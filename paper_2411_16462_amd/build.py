@@ -14,7 +14,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblioncub.so")
-SOURCES = ["lc_update_pack.hip", "lc_aggregate.hip", "lc_momentum_avg.hip", "lc_l1.hip", "lc_api.hip"]
+SOURCES = ["lc_update_pack.hip", "lc_aggregate.hip", "lc_momentum_avg.hip", "lc_l1.hip", "lc_probe.hip", "lc_api.hip"]
 HEADERS = [os.path.join(CSRC, "lc_common.hpp"), os.path.join(CSRC, "lc_launch.hpp"),
            os.path.join(ROOT, "include", "lioncub.h")]
 
@@ -44,7 +44,7 @@ def _compile(src, force, extra):
 def build(force=False, extra_flags=()):
     """Compile what is stale (everything if force) and link; returns the library path."""
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=5) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(lambda s: _compile(s, force, list(extra_flags)), SOURCES))
     if force or _stale(LIB, objs):
         tmp = LIB + ".tmp.%d" % os.getpid()

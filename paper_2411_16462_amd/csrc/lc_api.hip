@@ -666,6 +666,16 @@ const char *lc_status_string(int status)
     }
 }
 
+int lc_stream_probe(int kind, float *a, const float *b, size_t n, float s, void *stream)
+{
+    if (kind < LC_PROBE_READ || kind > LC_PROBE_RMW2) return LC_ERR_MODE;
+    if (n > LC_MAX_N) return LC_ERR_SIZE;
+    if (!a || ((kind == LC_PROBE_COPY || kind == LC_PROBE_RMW2) && !b)) return LC_ERR_NULL;
+    if (!aligned(a, 16) || !aligned(b, 16)) return LC_ERR_ALIGN;
+    if (n == 0) return LC_OK;
+    return from_hip(launch_stream_probe(kind, a, b, n, s, static_cast<hipStream_t>(stream)));
+}
+
 int lc_version(void) { return 100; }
 
 }  // extern "C"

@@ -65,6 +65,7 @@ hipError_t launch_local_update_pack(const void *g, size_t g_stride, int g_dtype,
 // kout: the counts K are wanted as fields from 1-bit rows.
 hipError_t launch_aggregate(const AggParams &P, int in_kind, bool apply, bool kout, int g_dtype, hipStream_t s);
 hipError_t launch_momentum_avg(float *m, size_t stride, int W, size_t n, hipStream_t s);
+hipError_t launch_stream_probe(int kind, float *a, const float *b, size_t n, float s, hipStream_t st);
 hipError_t launch_momentum_avg_ranges(float *m, size_t stride, int W, const size_t *offsets, const size_t *sizes, int n_ranges,
                                       hipStream_t s);
 // n_groups = 0: one maximum over the whole range; else one per segment of the group table

@@ -305,3 +305,17 @@ def test_static_workspace_entry_point_validation():
     assert lc.lc_l1_mean_abs_static(W=2, **{**a, "g_dtype": 7}) == lc.LC_ERR_DTYPE
     text = open(HEADER).read()
     assert int(re.search(r"#define LC_L1_STATIC_MAX_W (\d+)", text).group(1)) == lc.LC_L1_STATIC_MAX_W
+
+
+def test_stream_probe_validation():
+    probe = lambda **kw: lc.lc_stream_probe(**dict(dict(kind=lc.LC_PROBE_COPY, a=A, b=A + 4096, n=1000, s=1.0, stream=0, check=False), **kw))
+    text = open(HEADER).read()
+    for name in ("LC_PROBE_READ", "LC_PROBE_WRITE", "LC_PROBE_COPY", "LC_PROBE_SCALE", "LC_PROBE_RMW2"):
+        assert int(re.search(r"#define %s (\d+)" % name, text).group(1)) == getattr(lc, name)
+    assert probe(n=0) == lc.LC_OK
+    assert probe(kind=-1) == lc.LC_ERR_MODE and probe(kind=5) == lc.LC_ERR_MODE
+    assert probe(a=0) == lc.LC_ERR_NULL
+    assert probe(b=0) == lc.LC_ERR_NULL and probe(kind=lc.LC_PROBE_RMW2, b=0) == lc.LC_ERR_NULL
+    assert probe(kind=lc.LC_PROBE_READ, b=0, n=0) == lc.LC_OK          # b is optional where it is not read
+    assert probe(a=A + 4) == lc.LC_ERR_ALIGN and probe(b=A + 8) == lc.LC_ERR_ALIGN
+    assert probe(n=lc.LC_MAX_N + 1) == lc.LC_ERR_SIZE

@@ -54,6 +54,7 @@ def test_default_headline_is_the_largest_full_path_workload():
     finally:
         sys.argv = old
     assert args.workload == "c3" and args.others == "default" and args.copies == 2 and args.steps == 20
+    assert not args.no_ceilings and not args.divergence
     for key in ("c0", "c0rot", "c1", "c2", "c4", "c4sum"):
         wname, kw, copies, _ = bench.OTHERS[key]
         assert synth.workload(wname).name.startswith(key[:2])
