@@ -34,8 +34,9 @@ def device_asm(name, tmp_path):
 
 @pytest.mark.parametrize("source,pattern", [
     ("lc_update_pack", r"local_update_pack(_ternary)?_kernel"),
-    ("lc_momentum_avg", r"momentum_avg_kernel"),
+    ("lc_momentum_avg", r"momentum_(avg|avg_ranges|divergence)_kernel"),
     ("lc_l1", r"l1_(abs_sum|quantize_pack)_kernel"),
+    ("lc_probe", r"stream_probe_kernelILi[0234]E"),               # kind 1 only writes: checked like the others below
 ])
 def test_wide_accesses_are_non_temporal(source, pattern, tmp_path):
     kernels = {k: v for k, v in device_asm(source, tmp_path).items() if re.search(pattern, k)}
@@ -45,6 +46,32 @@ def test_wide_accesses_are_non_temporal(source, pattern, tmp_path):
         assert wide, name
         plain = [l for l in wide if not l.endswith(" nt")]
         assert not plain, "%s: %d of %d 16-byte accesses lost the non-temporal hint: %s" % (name, len(plain), len(wide), plain[:2])
+
+
+def test_divergence_kernel_requests_every_row_before_it_uses_one(tmp_path):
+    """The divergence kernel owes its speed to having all W <= CAP rows in flight at once (6.8 against 3.3 TB/s
+    when the compiler interleaves loads and arithmetic): in each register-resident instance the first wait for a
+    load must come after CAP 16-byte loads."""
+    out = os.path.join(str(tmp_path), "avg.s")
+    flags = [f for f in hip_build.FLAGS if f not in ("-fPIC", "-Wall", "-Wextra")]
+    subprocess.check_call([hip_build.HIPCC, *flags, "-S", "--cuda-device-only", os.path.join(CSRC, "lc_momentum_avg.hip"), "-o", out],
+                          stderr=subprocess.DEVNULL)
+    seen, cur, loads, done = {}, None, 0, False
+    for line in open(out):
+        m = re.match(r"^_ZN2lc26momentum_divergence_kernelILi(\d+)ELb([01])EEE\w*:", line)
+        if m:
+            cur, loads, done = (int(m.group(1)), int(m.group(2))), 0, False
+        elif cur and not done:
+            if re.search(r"\bglobal_load_dwordx4\b", line):
+                loads += 1
+            elif re.search(r"\bs_waitcnt vmcnt", line) and loads >= 4:      # (a grouped instance first waits for its table)
+                seen[cur] = loads
+                done = True
+        if line.startswith(".Lfunc_end"):
+            cur = None
+    assert set(seen) == {(c, g) for c in (4, 8, 16, 32, 64) for g in (0, 1)}, sorted(seen)
+    for (cap, grouped), n_loads in seen.items():
+        assert n_loads >= cap, "CAP = %d, grouped = %d: only %d loads before the first wait" % (cap, grouped, n_loads)
 
 
 def test_aggregate_theta_and_momentum_streams_are_non_temporal(tmp_path):
