@@ -697,6 +697,10 @@ def main():
         del r
         torch.cuda.empty_cache()
     out["configs"] = configs
+    if ceil is not None:  # every kernel also against the bare copy kernel of this run
+        for rows in [out["kernels"]] + [e["kernels"] for e in configs.values()]:
+            for k in rows:
+                k["frac_of_measured_copy"] = k["achieved_GBps"] / ceil["copy"]
     print(json.dumps(out))
 
 
