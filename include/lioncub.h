@@ -31,7 +31,10 @@
  *    aligned.  1-bit buffers and vote planes: 8-byte aligned.  (Speed, not correctness:
  *    rows that start a large power of two apart -- a row stride of exactly 64 MiB, say --
  *    fall on the same memory channels; measured with 64 rows that costs a fifth of the
- *    bandwidth.  Pad the stride by a few hundred bytes in that case.)
+ *    bandwidth; pad the stride in that case.  And the float rows stream best when their
+ *    stride is a multiple of 1 KiB, so that every 256-element tile of every row is aligned
+ *    alike: measured 4 % on lc_momentum_avg with 16 rows.  So pad to a multiple of 1 KiB
+ *    that is not a multiple of a large power of two.)
  *  - `step` is the caller's 1-based iteration counter; only its parity is used, by the
  *    alternating rule of Appendix B.1 (zero -> +1 on odd iterations, -1 on even ones).
  *  - Buffers named in one call must not overlap each other.
