@@ -150,8 +150,8 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
             # the two halves as a multi-GPU run would call them around the allgather of the
             # vote: planes out, then planes in.  one_plane: the 1-bit wire form (a tie takes
             # the alternating sign, so one plane carries the whole vote)
-            pos = torch.zeros(synth.round_up(nw, synth.WORD_ALIGN), dtype=torch.int64, device=dev)
-            nz = None if one_plane else torch.zeros(synth.round_up(nw, synth.WORD_ALIGN), dtype=torch.int64, device=dev)
+            pos = torch.zeros(synth.packed_row_words(nw), dtype=torch.int64, device=dev)
+            nz = None if one_plane else torch.zeros(synth.packed_row_words(nw), dtype=torch.int64, device=dev)
             tie = lc.LC_TIE_ALT if one_plane else lc.LC_TIE_ZERO
             planes = 1 if one_plane else 2
             st.update(pos=pos, nz=nz)
@@ -191,7 +191,7 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
     gb = 2 if wl.g_dtype == "bf16" else 4
     st.update(theta=theta, m=m, g=g)
     if wl.mode == "1bit" and per_tensor and wl.tensors:
-        q = torch.zeros((W, synth.round_up(nw, synth.WORD_ALIGN)), dtype=torch.int64, device=dev)
+        q = torch.zeros((W, synth.packed_row_words(nw, W)), dtype=torch.int64, device=dev)
         st["q"] = q
         spans, off = [], 0
         for _, sz in wl.tensors:
@@ -211,7 +211,7 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
         kernels.append(Kernel("local_update_pack[per tensor]", pack_all, W * n * (4 + gb + 4 + 1 / 8)))
         kernels.append(Kernel("vote_apply_1bit[per tensor]", vote_all, n * (W / 8 + 8)))
     elif wl.mode == "1bit":
-        q = torch.zeros((W, synth.round_up(nw, synth.WORD_ALIGN)), dtype=torch.int64, device=dev)
+        q = torch.zeros((W, synth.packed_row_words(nw, W)), dtype=torch.int64, device=dev)
         st["q"] = q
         kernels.append(Kernel(
             "local_update_pack",
@@ -233,8 +233,8 @@ def build_step(wl, torch, lc, synth, per_tensor=False, groups=False, split=False
                                               hp["wd"], None, 0, None, 0, lc.LC_F32, 0, hp["beta2"]),
                 n * (W / 8 + 8)))
     elif wl.mode == "ternary":
-        pos = torch.zeros((W, synth.round_up(nw, synth.WORD_ALIGN)), dtype=torch.int64, device=dev)
-        nz = torch.zeros((W, synth.round_up(nw, synth.WORD_ALIGN)), dtype=torch.int64, device=dev)
+        pos = torch.zeros((W, synth.packed_row_words(nw, W)), dtype=torch.int64, device=dev)
+        nz = torch.zeros((W, synth.packed_row_words(nw, W)), dtype=torch.int64, device=dev)
         st.update(pos=pos, nz=nz)
         kernels.append(Kernel(
             "local_update_pack_ternary",

@@ -34,7 +34,8 @@
  *    bandwidth; pad the stride in that case.  And the float rows stream best when their
  *    stride is a multiple of 1 KiB, so that every 256-element tile of every row is aligned
  *    alike: measured 4 % on lc_momentum_avg with 16 rows.  So pad to a multiple of 1 KiB
- *    that is not a multiple of a large power of two.)
+ *    that is not a multiple of a large power of two.  1-bit rows: an odd number of 128-byte
+ *    lines per row for up to 24 rows, an odd number of 64-byte units for 32 and more.)
  *  - `step` is the caller's 1-based iteration counter; only its parity is used, by the
  *    alternating rule of Appendix B.1 (zero -> +1 on odd iterations, -1 on even ones).
  *  - Buffers named in one call must not overlap each other.

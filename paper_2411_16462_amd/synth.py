@@ -20,11 +20,22 @@ from typing import List, Optional, Tuple
 import torch
 
 ROW_ALIGN = 64  # elements; keeps every worker's row 256-byte aligned for fp32
-WORD_ALIGN = 8   # 64-bit words; packed rows start 64-byte aligned
+WORD_ALIGN = 16  # 64-bit words in a 128-byte line; see packed_row_words
 
 
 def round_up(x: int, a: int) -> int:
     return (x + a - 1) // a * a
+
+
+def packed_row_words(nw, W=1):
+    """Row stride, in 64-bit words, for W rows of nw packed words.  Measured on the MI355X: the kernels
+    that walk many rows per wave (32 and more) run fastest when the largest power of two that divides the
+    stride is small -- 64 rows at c4's size: 5.85 ms at an odd multiple of 64 bytes, 6.05 at one of 128 or
+    256, 6.25 at 512, 6.65 at 4 KiB -- so those get an odd number of 64-byte units; the few-worker kernel
+    reads whole 128-byte lines of every row per workgroup and gains 2 % from rows that are whole lines, so
+    fewer rows get an odd number of 128-byte lines."""
+    unit = WORD_ALIGN // 2 if W >= 32 else WORD_ALIGN
+    return ((max(nw, 1) + unit - 1) // unit | 1) * unit
 
 
 def gpt2_tensors(d: int, n_layer: int, vocab: int = 50257, n_pos: int = 1024
@@ -169,7 +180,7 @@ def make_prepacked(n: int, W: int, *, seed: int, device="cpu", agree: float = 0.
     lo, hi = -(1 << 63), (1 << 63) - 1
     latent = torch.randint(lo, hi, (nw,), generator=gen, device=device, dtype=torch.int64)
     flip_num = round((1.0 - agree) * (1 << prob_bits))
-    q = torch.zeros((W, round_up(max(nw, 1), WORD_ALIGN)), dtype=torch.int64, device=device)[:, :nw]
+    q = torch.zeros((W, packed_row_words(nw, W)), dtype=torch.int64, device=device)[:, :nw]
     tail = n % 64
     for w in range(W):
         q[w] = latent ^ biased_words(nw, flip_num, prob_bits, gen, device)

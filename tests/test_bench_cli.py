@@ -60,3 +60,12 @@ def test_default_headline_is_the_largest_full_path_workload():
         assert synth.workload(wname).name.startswith(key[:2])
     assert bench.OTHERS["c4sum"][1] == {"variant": "sum"} and bench.OTHERS["c0rot"][2] == 8
     assert bench.stats([3.0, 1.0, 2.0, 10.0]) == {"mean": 4.0, "median": 2.5, "min": 1.0}
+
+
+def test_packed_row_strides_follow_the_measured_rule():
+    """Few rows: an odd number of whole 128-byte lines; 32 and more rows: an odd number of 64-byte units."""
+    for nw in (0, 1, 7, 16, 17, 1944372, 5544112, 20312500):
+        few, many = synth.packed_row_words(nw, 8), synth.packed_row_words(nw, 64)
+        assert few >= max(nw, 1) and few % 16 == 0 and (few // 16) % 2 == 1 and few - nw < 32
+        assert many >= max(nw, 1) and many % 8 == 0 and (many // 8) % 2 == 1 and many - nw < 16
+    assert synth.packed_row_words(20312500, 64) == 20312504 and synth.packed_row_words(5544112, 16) == 5544112
