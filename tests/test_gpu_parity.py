@@ -388,6 +388,33 @@ def test_momentum_divergence(W, n):
     assert float(out[0]) == 0.0
 
 
+@pytest.mark.parametrize("W", [3, 16, 40, 70])
+def test_momentum_divergence_special_values(W):
+    """Elements that hold a NaN or an infinity have no standard deviation and take no part in the
+    maximum (the comparison with a NaN is false on both sides); denormals and huge values do."""
+    n = 5000
+    case = Case(n, W, seed=14300 + W, m_spread=0.3)
+    case.m[0, 10] = float("nan")
+    case.m[W - 1, 11] = float("inf")
+    case.m[1, 12] = -float("inf")
+    case.m[:, 300] = torch.linspace(-1e-41, 1e-41, W)          # denormals
+    case.m[:, 4000] = torch.linspace(-1.0, 1.0, W) * 1e18       # the maximum sits here
+    case.m[:, 256 * 19 + 3] = float("nan")                       # a whole column, in the ragged last tile
+    case.snapshot()
+    out = torch.full((1,), -1.0, dtype=torch.float64, device="cuda")
+    lc.lc_momentum_divergence(case.m, case.m.stride(0), W, n, out)
+    torch.cuda.synchronize()
+    ref = orc.momentum_divergence(case.m0)
+    assert ref > 1e17 and np.isfinite(ref) and abs(float(out[0]) - ref) <= 1e-12 * ref
+    end_t = torch.tensor([4, 63, (n + 63) // 64], dtype=torch.int32, device="cuda")
+    outg = torch.full((3,), -1.0, dtype=torch.float64, device="cuda")
+    lc.lc_momentum_divergence_groups(case.m, case.m.stride(0), W, n, end_t, 3, outg)
+    torch.cuda.synchronize()
+    for s, (lo, hi) in enumerate(((0, 256), (256, 4032), (4032, n))):
+        r = orc.momentum_divergence(case.m0[:, lo:hi])
+        assert abs(float(outg[s]) - r) <= 1e-12 * r, (s, float(outg[s]), r)
+
+
 @pytest.mark.parametrize("W", [2, 5, 16])
 def test_momentum_divergence_per_group(W):
     """The same metric for every segment of a group table in one launch (Figure 6 is per
